@@ -1,0 +1,330 @@
+/*
+ * gq_oracle.c -- plain CPU reference ("oracle") for the Global-QSGD data-parallel hot path.
+ *
+ * TEST INFRASTRUCTURE, NOT PRODUCT.  Only the test-suite, the smoke check and the benchmark's
+ * cpu_baseline leg may load this file.  It shares no code, header, table or helper with the HIP
+ * library; the HIP library never calls it.  Everything is scalar C, one coordinate at a time, in
+ * the order the paper states the steps, so that it can be checked against the paper by eye.
+ *
+ * What it follows (arXiv 2305.18627):
+ *   Algorithm 1 line 1      global norm of the concatenation [x_1 .. x_n]          -> gqo_global_norm
+ *   Algorithm 1 lines 2-5,  y = |x| / norm, z = sign(x) o xi(y) with the random
+ *   Definition 1, Eq. (2)   rounding xi to one of the two neighbouring levels      -> gqo_linear_code, gqo_exp_code
+ *   Section 4.2             linear grid l_i = (s-i)/s; exponential grid 0 and 2^-j -> same two functions
+ *   Section 4.2 / Sec. 7    8-bit and packed 4-bit storage of the level integers   -> gqo_pack, gqo_unpack
+ *   Algorithm 1 line 9      aggregation = plain sum of the level integers          -> gqo_aggregate
+ *   Section 4.2             headroom rule for the sum at a given integer width     -> gqo_check_width, gqo_fits_width
+ *   Eq. (1)                 norm * (1/n) * sum                                     -> gqo_dequantize
+ *
+ * Stored level integer ("code").  The paper numbers levels downwards, l_0 = 1 > ... > l_s = 0.
+ * The integer that is stored and summed is k = s - u for level l_u, so k = 0 is the zero level:
+ *   linear:       k in 0..s  stands for k/s                      integer value  V(k) = k
+ *   exponential:  k = 0 stands for 0, k in 1..s for 2^(k-s)      integer value  V(k) = 2^(k-1)
+ *                                                                (in units of the smallest level 2^-(s-1))
+ * The signed code is q = sign(x) * k.
+ *
+ * Readings of the paper taken here (the paper is silent or inconsistent on these):
+ *   - exponential grid: printed as l_i = 1/2^(s-i), which contradicts l_0 = 1; the proof of
+ *     Theorem 1 says the segment next to zero has length 2^-(s-1).  Grid used: {0} u {2^-j, j=0..s-1}.
+ *   - "global L2 norm" is the (2,2) mixed norm = L2 norm of the concatenation; "global max norm"
+ *     is (inf,inf).  (2,inf) = max of per-worker L2 norms (the literal line 1) is offered as well.
+ *   - exponential aggregation is the exact integer sum of V(k) (Algorithm 2's stochastic
+ *     re-rounding is a different wire format and is not part of this path).
+ *   - random numbers: Eq. (2) only fixes probabilities.  The draw is 32 bits r per (worker,
+ *     coordinate) from Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11) with
+ *     counter = (lo32(g/4), hi32(g/4), worker, 0), key = (lo32(seed), hi32(seed)), word g mod 4,
+ *     g = index_base + j the global coordinate index.
+ *       linear:  U' = fl32(fl32(r) * c), c = 2^-32 - 2^-56 the largest binary32 below 2^-32, so that
+ *                0 <= U' < 1 with the relative resolution of binary32 near 0;
+ *                v = fl32(|x| * scale - U') with ONE rounding (fused multiply-add),
+ *                scale = fl32(s / norm);  k = min(ceil(v), s).
+ *                So k = h+1 exactly when U' < frac part, which has probability y*s - h as Eq. (2)
+ *                asks, up to the binary32 granularity of U' and of v (a coordinate that sits on
+ *                level k stays there with probability >= 1 - k*2^-23, with certainty for k <= 1).
+ *       exp:     z = fl32(|x| * scale), scale = fl32(2^(s-1) / norm), clamped to 2^(s-1);  R = r >> 9.
+ *                z >= 1: z = 2^e * (1 + m/2^23); round up iff m + R >= 2^23: probability m/2^23 =
+ *                (z - 2^e)/2^e exactly as Eq. (2) asks.   z < 1: m = z*2^23 rounded to nearest
+ *                integer (ties to even); round up to the smallest level iff m + R >= 2^23.
+ *   - top of the range: |x| = norm can land one ulp above s after rounding; the code is clamped to s.
+ *   - norm == 0, norm not finite, or scale not finite: every code is 0.
+ *
+ * Floating point: the two decisions that turn a float into an integer (ceil(v), the carry out of
+ * m + R) are taken in IEEE binary32 exactly as written, because that is the precision the method
+ * runs in; compile with -ffp-contract=off so that nothing else is fused.  Norm and dequantised
+ * values are computed in binary64.
+ */
+#include <stdint.h>
+#include <stddef.h>
+#include <string.h>
+#include <stdlib.h>
+#include <math.h>
+#include <float.h>
+
+enum { GQO_LINEAR = 0, GQO_EXP = 1 };
+enum { GQO_NORM_LINF = 0, GQO_NORM_L2 = 1, GQO_NORM_L2_MAX = 2 };
+enum { GQO_PACK_I8 = 0, GQO_PACK_I4 = 1, GQO_PACK_U8_SIGNPLANE = 2, GQO_PACK_U4_SIGNPLANE = 3 };
+
+/* ------------------------------------------------------------------------------------------
+ * Philox4x32 with `rounds` rounds (Salmon et al., SC'11, Section 3.3 / Table 2 constants).
+ * One round: two 32x32->64 products, the high halves are xored with the other two counter
+ * words and the round key, the low halves pass through; the key is bumped between rounds.
+ * ------------------------------------------------------------------------------------------ */
+void gqo_philox4x32(int rounds, const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    const uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;   /* multipliers */
+    const uint32_t W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;   /* Weyl key increments */
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int r = 0; r < rounds; r++) {
+        if (r > 0) { k0 += W0; k1 += W1; }
+        uint64_t p0 = (uint64_t)M0 * (uint64_t)c0;
+        uint64_t p1 = (uint64_t)M1 * (uint64_t)c2;
+        uint32_t hi0 = (uint32_t)(p0 >> 32), lo0 = (uint32_t)p0;
+        uint32_t hi1 = (uint32_t)(p1 >> 32), lo1 = (uint32_t)p1;
+        uint32_t n0 = hi1 ^ c1 ^ k0;
+        uint32_t n1 = lo1;
+        uint32_t n2 = hi0 ^ c3 ^ k1;
+        uint32_t n3 = lo0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* The 32 random bits of (seed, worker, global coordinate index g). */
+uint32_t gqo_random_word(uint64_t seed, uint32_t worker, uint64_t g)
+{
+    uint64_t call = g / 4u;
+    uint32_t ctr[4] = { (uint32_t)call, (uint32_t)(call >> 32), worker, 0u };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t out[4];
+    gqo_philox4x32(10, ctr, key, out);
+    return out[g % 4u];
+}
+
+void gqo_random_words(uint64_t seed, uint32_t worker, uint64_t index_base, int64_t d, uint32_t *r)
+{
+    for (int64_t j = 0; j < d; j++) r[j] = gqo_random_word(seed, worker, index_base + (uint64_t)j);
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Algorithm 1 line 1: the global norm.  Returns flag bits: 1 = norm not finite, 2 = norm zero.
+ * ------------------------------------------------------------------------------------------ */
+int gqo_global_norm(const float *const *x, int K, int64_t d, int kind, double *norm_exact, float *norm_f32)
+{
+    double result = 0.0;
+    if (kind == GQO_NORM_LINF) {
+        for (int i = 0; i < K; i++)
+            for (int64_t j = 0; j < d; j++) {
+                double a = fabs((double)x[i][j]);
+                if (a != a) result = a;                       /* NaN is sticky */
+                else if (!(result != result) && a > result) result = a;
+            }
+    } else if (kind == GQO_NORM_L2) {
+        double acc = 0.0;
+        for (int i = 0; i < K; i++)
+            for (int64_t j = 0; j < d; j++) acc += (double)x[i][j] * (double)x[i][j];
+        result = sqrt(acc);
+    } else {                                                  /* (2,inf): max over workers of ||x_i||_2 */
+        for (int i = 0; i < K; i++) {
+            double acc = 0.0;
+            for (int64_t j = 0; j < d; j++) acc += (double)x[i][j] * (double)x[i][j];
+            double ni = sqrt(acc);
+            if (ni != ni) result = ni;
+            else if (!(result != result) && ni > result) result = ni;
+        }
+    }
+    *norm_exact = result;
+    *norm_f32 = (float)result;
+    int flags = 0;
+    if (!(fabs((double)*norm_f32) <= FLT_MAX)) flags |= 1;
+    if (*norm_f32 == 0.0f) flags |= 2;
+    return flags;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Eq. (2) on the linear grid l_u = (s-u)/s.  With t = y*s, the neighbours of y are h/s and
+ * (h+1)/s, h = floor(t), and the upper one is taken with probability t - h.
+ * ------------------------------------------------------------------------------------------ */
+int32_t gqo_linear_code(float x, float norm, int s, uint32_t r)
+{
+    if (!(norm > 0.0f)) return 0;
+    float scale = (float)s / norm;
+    if (!(scale <= FLT_MAX)) return 0;
+    float u = (float)r * 0x1.fffffep-33f;          /* U' in [0,1): fl32(r) times the largest float below 2^-32 */
+    float v = fmaf(fabsf(x), scale, -u);           /* t - U' with one rounding */
+    if (v != v) return 0;
+    float c = ceilf(v);                            /* = h+1 iff U' < t-h, else h; never negative as U' < 1 */
+    if (c > (float)s) c = (float)s;
+    int32_t k = (int32_t)c;
+    return (x < 0.0f) ? -k : k;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Eq. (2) on the exponential grid {0} u {2^-j : j = 0..s-1}.  z = y * 2^(s-1) measures y in
+ * units of the smallest non-zero level, so the grid in z is 0, 1, 2, 4, .., 2^(s-1).
+ * ------------------------------------------------------------------------------------------ */
+int32_t gqo_exp_code(float x, float norm, int s, uint32_t r)
+{
+    if (!(norm > 0.0f)) return 0;
+    float top = ldexpf(1.0f, s - 1);
+    float scale = top / norm;
+    if (!(scale <= FLT_MAX)) return 0;
+    float z = fabsf(x) * scale;
+    if (z != z) return 0;
+    if (z > top) z = top;
+    uint32_t R = r >> 9;                            /* 23 dither bits */
+    int32_t k;
+    if (z >= 1.0f) {
+        /* 2^e <= z < 2^(e+1): lower level code e+1, upper e+2, P(up) = (z-2^e)/2^e = m/2^23 */
+        uint32_t bits; memcpy(&bits, &z, 4);
+        int32_t e = (int32_t)(bits >> 23) - 127;
+        uint32_t m = bits & 0x7FFFFFu;
+        k = e + 1 + (int32_t)((m + R) >> 23);
+    } else {
+        /* 0 <= z < 1: lower level 0, upper level code 1, P(up) = z, resolved to 2^-23 */
+        uint32_t m = (uint32_t)lrintf(z * 0x1p23f);   /* nearest, ties to even; at most 2^23 */
+        k = (int32_t)((m + R) >> 23);
+    }
+    if (k > s) k = s;
+    return (x < 0.0f) ? -k : k;
+}
+
+int32_t gqo_code(int scheme, float x, float norm, int s, uint32_t r)
+{
+    return scheme == GQO_LINEAR ? gqo_linear_code(x, norm, s, r) : gqo_exp_code(x, norm, s, r);
+}
+
+/* Codes for given random words (the words are an input: used by the rounding-law tests). */
+void gqo_quantize_with_words(const float *x, const uint32_t *r, int64_t d, float norm,
+                             int scheme, int s, int32_t *q)
+{
+    for (int64_t j = 0; j < d; j++) q[j] = gqo_code(scheme, x[j], norm, s, r[j]);
+}
+
+/* Algorithm 1 lines 2-5 for one worker. */
+void gqo_quantize(const float *x, int64_t d, float norm, int scheme, int s,
+                  uint64_t seed, uint32_t worker, uint64_t index_base, int32_t *q)
+{
+    for (int64_t j = 0; j < d; j++)
+        q[j] = gqo_code(scheme, x[j], norm, s, gqo_random_word(seed, worker, index_base + (uint64_t)j));
+}
+
+/* Signed integer value that a signed code contributes to the sum. */
+int64_t gqo_code_value(int scheme, int32_t q)
+{
+    if (scheme == GQO_LINEAR || q == 0) return (int64_t)q;
+    int32_t k = q < 0 ? -q : q;
+    int64_t v = (int64_t)1 << (k - 1);
+    return q < 0 ? -v : v;
+}
+
+/* Algorithm 1 line 9: A_j = sum_i V(q_ij), accumulated in 64 bits. */
+void gqo_aggregate(const int32_t *const *q, int K, int64_t d, int scheme, int64_t *A)
+{
+    for (int64_t j = 0; j < d; j++) {
+        int64_t acc = 0;
+        for (int i = 0; i < K; i++) acc += gqo_code_value(scheme, q[i][j]);
+        A[j] = acc;
+    }
+}
+
+/* Largest magnitude the sum of K codes can reach: linear K*s, exponential K*2^(s-1). */
+int64_t gqo_max_aggregate(int scheme, int s, int K)
+{
+    if (scheme == GQO_LINEAR) return (int64_t)K * s;
+    if (s > 55) return INT64_MAX;
+    return (int64_t)K * ((int64_t)1 << (s - 1));
+}
+
+/* 1 if a signed integer of `bits` bits always holds the sum, else 0. */
+int gqo_check_width(int scheme, int s, int K, int bits)
+{
+    int64_t lim = ((int64_t)1 << (bits - 1)) - 1;
+    return gqo_max_aggregate(scheme, s, K) <= lim;
+}
+
+/* 1 if every A_j fits a signed integer of `bits` bits. */
+int gqo_fits_width(const int64_t *A, int64_t d, int bits)
+{
+    int64_t lim = ((int64_t)1 << (bits - 1)) - 1;
+    for (int64_t j = 0; j < d; j++) if (A[j] > lim || A[j] < -lim - 1) return 0;
+    return 1;
+}
+
+/* Eq. (1): norm * (1/n) * sum, with the grid's unit (1/s or 2^-(s-1)) put back. */
+void gqo_dequantize(const int64_t *A, int64_t d, double norm, int scheme, int s, int K, double *out)
+{
+    double unit = scheme == GQO_LINEAR ? 1.0 / (double)s : ldexp(1.0, -(s - 1));
+    for (int64_t j = 0; j < d; j++) out[j] = norm * ((double)A[j] * unit) / (double)K;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Storage of signed codes.
+ *   I8            byte j = q_j as two's complement                                  (s <= 127)
+ *   I4            byte b = (q_2b & 15) | (q_2b+1 & 15) << 4, two's complement nibbles (s <= 7);
+ *                 an odd d leaves the last high nibble 0
+ *   U8_SIGNPLANE  byte j = |q_j| (s <= 255); sign word w bit t = 1 iff q_(32w+t) < 0
+ *   U4_SIGNPLANE  nibbles as I4 but holding |q| (s <= 15); same sign words
+ * Returns 0, or -1 if a code does not fit the format.
+ * ------------------------------------------------------------------------------------------ */
+int64_t gqo_levels_bytes(int64_t d, int pack)
+{
+    return (pack == GQO_PACK_I8 || pack == GQO_PACK_U8_SIGNPLANE) ? d : (d + 1) / 2;
+}
+int64_t gqo_signplane_words(int64_t d) { return (d + 31) / 32; }
+
+int gqo_pack(const int32_t *q, int64_t d, int pack, uint8_t *levels, uint32_t *signplane)
+{
+    int has_plane = (pack == GQO_PACK_U8_SIGNPLANE || pack == GQO_PACK_U4_SIGNPLANE);
+    int nib = (pack == GQO_PACK_I4 || pack == GQO_PACK_U4_SIGNPLANE);
+    memset(levels, 0, (size_t)gqo_levels_bytes(d, pack));
+    if (has_plane) memset(signplane, 0, (size_t)gqo_signplane_words(d) * 4);
+    for (int64_t j = 0; j < d; j++) {
+        int32_t v = q[j], mag = v < 0 ? -v : v;
+        int32_t lim = pack == GQO_PACK_I8 ? 127 : pack == GQO_PACK_I4 ? 7 : pack == GQO_PACK_U8_SIGNPLANE ? 255 : 15;
+        if (mag > lim) return -1;
+        uint32_t field = has_plane ? (uint32_t)mag : (uint32_t)v;
+        if (nib) levels[j / 2] |= (uint8_t)((field & 15u) << (4 * (j % 2)));
+        else     levels[j] = (uint8_t)(field & 255u);
+        if (has_plane && v < 0) signplane[j / 32] |= (uint32_t)1 << (j % 32);
+    }
+    return 0;
+}
+
+void gqo_unpack(const uint8_t *levels, const uint32_t *signplane, int64_t d, int pack, int32_t *q)
+{
+    for (int64_t j = 0; j < d; j++) {
+        int32_t v;
+        if (pack == GQO_PACK_I8) v = (int8_t)levels[j];
+        else if (pack == GQO_PACK_U8_SIGNPLANE) v = levels[j];
+        else {
+            uint32_t n = (levels[j / 2] >> (4 * (j % 2))) & 15u;
+            v = (pack == GQO_PACK_I4 && n >= 8) ? (int32_t)n - 16 : (int32_t)n;
+        }
+        if ((pack == GQO_PACK_U8_SIGNPLANE || pack == GQO_PACK_U4_SIGNPLANE) &&
+            ((signplane[j / 32] >> (j % 32)) & 1u)) v = -v;
+        q[j] = v;
+    }
+}
+
+/* ------------------------------------------------------------------------------------------
+ * The whole path for K workers, as the composition of the steps above (no fusion here):
+ * quantize each worker, sum.  Used for parity of the fused GPU call and for the CPU timing.
+ * Returns 0, or -1 if memory for the K code vectors could not be had.
+ * ------------------------------------------------------------------------------------------ */
+int gqo_quantize_aggregate(const float *const *x, int K, int64_t d, float norm, int scheme, int s,
+                           uint64_t seed, uint64_t index_base, int64_t *A)
+{
+    int32_t **q = (int32_t **)calloc((size_t)K, sizeof(int32_t *));
+    if (!q) return -1;
+    int rc = 0;
+    for (int i = 0; i < K; i++) {
+        q[i] = (int32_t *)malloc((size_t)(d > 0 ? d : 1) * sizeof(int32_t));
+        if (!q[i]) { rc = -1; break; }
+        gqo_quantize(x[i], d, norm, scheme, s, seed, (uint32_t)i, index_base, q[i]);
+    }
+    if (rc == 0) gqo_aggregate((const int32_t *const *)q, K, d, scheme, A);
+    for (int i = 0; i < K; i++) free(q[i]);
+    free(q);
+    return rc;
+}
