@@ -1,0 +1,161 @@
+/*
+ * gqsgd.h -- C ABI of the MI355X (gfx950) library for the data-parallel hot path of Global-QSGD
+ * (arXiv 2305.18627): global norm -> stochastic rounding to integer levels -> integer sum over
+ * workers -> dequantisation, plus the fused quantize+aggregate call.
+ *
+ * One GPU, one process.  The n = K workers of the paper's Algorithm 1 are K gradient buffers
+ * resident on the same device.
+ *
+ * Conventions that hold for every call
+ *   pointers   Every data pointer is a DEVICE pointer unless its comment says "host".  Arrays of
+ *              per-worker pointers (x, levels, ...) are HOST arrays of K DEVICE pointers; they are
+ *              read during the call only.  The caller owns every buffer; the library allocates
+ *              nothing and keeps no pointer after a call returns.
+ *   alignment  Gradient, level, aggregate and output buffers must be 16-byte aligned, sign planes
+ *              and the norm 4-byte aligned, the norm workspace 8-byte aligned.
+ *   stream     `hip_stream` is a hipStream_t (NULL = the default stream).  Calls only enqueue work
+ *              and never synchronise; the norm stays on the device so that the norm pass and the
+ *              quantisation pass need no host round trip.
+ *   errors     Argument errors are returned synchronously and nothing is enqueued.  A launch
+ *              failure is returned as GQ_ERR_DEVICE.  Conditions that depend on the data are
+ *              reported through the device word `status_flags` of gq_global_norm.
+ *   sizes      1 <= K <= GQ_MAX_WORKERS, d >= 0 (d = 0 is a valid no-op), any d (ragged tails are
+ *              handled inside), index_base >= 0 and a multiple of 4.
+ *
+ * The stored integer ("code").  The paper numbers levels downwards, l_0 = 1 > ... > l_s = 0
+ * (Definition 1).  The integer stored and summed is k = s - u for level l_u, signed with sign(x):
+ *   linear grid       k in 0..s stands for k/s                   adds  k         to the sum
+ *   exponential grid  k = 0 stands for 0, k in 1..s for 2^(k-s)  adds  2^(k-1)   to the sum
+ * (Section 4.2; the exponential grid is read as {0} u {2^-j, j = 0..s-1}).
+ *
+ * Random rounding.  Eq. (2) fixes probabilities only.  Every (worker, coordinate) draws 32 bits r
+ * from Philox4x32-10 (Salmon et al., SC'11): counter (lo32(g/4), hi32(g/4), worker, 0), key
+ * (lo32(seed), hi32(seed)), word g mod 4, where g = index_base + j is the global coordinate index.
+ *   linear       U' = fl32(fl32(r) * (2^-32 - 2^-56));  v = fma(|x|, fl32(s/norm), -U');  k = min(ceil(v), s)
+ *   exponential  z = min(fl32(|x| * fl32(2^(s-1)/norm)), 2^(s-1));  R = r >> 9;
+ *                z >= 1: round the binary32 z up to the next power of two iff mantissa + R >= 2^23;
+ *                z <  1: k = 1 iff rne(z * 2^23) + R >= 2^23, else 0
+ * A norm that is zero or not finite (or so small that the scale overflows) gives all-zero codes.
+ * Inputs must be finite with |x| <= norm; otherwise codes stay within [-s, s] but are unspecified.
+ */
+#ifndef GQSGD_H
+#define GQSGD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GQ_MAX_WORKERS 64
+
+typedef enum {
+    GQ_OK = 0,
+    GQ_ERR_INVALID_ARG = 1,  /* NULL / misaligned pointer, K or d or index_base out of range, bad enum */
+    GQ_ERR_UNSUPPORTED = 2,  /* s does not fit the pack format, or a combination that is not built   */
+    GQ_ERR_OVERFLOW = 3,     /* the integer sum of K codes can exceed the aggregate width            */
+    GQ_ERR_WORKSPACE = 4,    /* workspace NULL or smaller than gq_norm_workspace_bytes               */
+    GQ_ERR_DEVICE = 5        /* the HIP runtime reported an error at launch                          */
+} gq_status;
+
+/* Mixed norms ||[x_1..x_n]||_{q,p} of Section 4.1 that Algorithm 1 line 1 may use. */
+typedef enum {
+    GQ_NORM_LINF = 0,   /* (inf,inf): max |x_ij| over all workers and coordinates (the paper's default) */
+    GQ_NORM_L2 = 1,     /* (2,2):     L2 norm of the concatenation                                      */
+    GQ_NORM_L2_MAX = 2  /* (2,inf):   max over workers of ||x_i||_2 (line 1 read literally)             */
+} gq_norm_kind;
+
+typedef enum { GQ_LINEAR = 0, GQ_EXP = 1 } gq_scheme;           /* level grid, Section 4.2 */
+
+/* Storage of the signed codes of one worker (Section 4.2 "8-bit", Section 7 "pack 4-bit into 8-bit").
+ *   I8            byte j = q_j, two's complement                                       needs s <= 127
+ *   I4            byte b = (q_2b & 15) | (q_2b+1 & 15) << 4, two's complement nibbles   needs s <= 7
+ *                 (an odd d leaves the last high nibble 0)
+ *   U8_SIGNPLANE  byte j = |q_j|; sign word w, bit t = 1 iff q_(32w+t) < 0              needs s <= 255
+ *   U4_SIGNPLANE  nibbles as I4 holding |q|; same sign words                            needs s <= 15
+ * Level buffers hold d (8-bit) or ceil(d/2) (4-bit) bytes, sign planes ceil(d/32) uint32 words;
+ * pad bits are written as 0. */
+typedef enum { GQ_PACK_I8 = 0, GQ_PACK_I4 = 1, GQ_PACK_U8_SIGNPLANE = 2, GQ_PACK_U4_SIGNPLANE = 3 } gq_pack;
+
+typedef enum { GQ_AGG_I32 = 0, GQ_AGG_I16 = 1 } gq_agg;         /* width of the integer sum */
+
+typedef struct {
+    int32_t scheme;   /* gq_scheme                                                        */
+    int32_t s;        /* number of non-zero levels, s >= 1 (exponential: s <= 31)          */
+    int32_t pack;     /* gq_pack: format of level buffers (ignored where none is touched) */
+    int32_t agg;      /* gq_agg: format of the integer sum (ignored where none is touched) */
+    uint64_t seed;    /* Philox key                                                       */
+} gq_params;
+
+/* Library version (major * 1000 + minor). */
+int gq_version(void);
+
+/* Static, human-readable name of a status code. */
+const char *gq_status_string(gq_status st);
+
+/* Section 4.2, integer headroom: GQ_OK if a signed integer of p->agg's width always holds the sum
+ * of K codes, i.e. K*s (linear) or K*2^(s-1) (exponential) <= 2^(A-1)-1; GQ_ERR_OVERFLOW if not;
+ * GQ_ERR_INVALID_ARG for bad parameters.  Host only, touches no device. */
+gq_status gq_check_width(const gq_params *p /* host */, int K);
+
+/* Bytes of device workspace gq_global_norm needs for (K, d); 0 if K or d is out of range. */
+size_t gq_norm_workspace_bytes(int K, int64_t d);
+
+/* Algorithm 1 line 1: the global norm of K gradients of d coordinates each.
+ *   x             host array of K device pointers to fp32[d]
+ *   norm_out      device fp32[1]: the norm, rounded once from a binary64 reduction (LINF is exact)
+ *   status_flags  device uint32[1] or NULL: overwritten with bit0 = norm is not finite (a NaN or
+ *                 Inf somewhere in x, or overflow), bit1 = norm is zero (every code will be 0)
+ *   workspace     device scratch of at least gq_norm_workspace_bytes(K, d) bytes; contents are
+ *                 overwritten; must not be shared by calls that may run concurrently
+ * The result does not depend on scheduling (no atomics): equal inputs give equal bits. */
+gq_status gq_global_norm(const float *const *x /* host */, int K, int64_t d, gq_norm_kind kind,
+                         float *norm_out, uint32_t *status_flags,
+                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Algorithm 1 lines 2-5 for ONE worker: y = |x|/norm, code = sign(x) * xi(y) (Definition 1, Eq. (2)).
+ *   x              device fp32[d]
+ *   norm           device fp32[1] (as written by gq_global_norm)
+ *   worker         the worker word of the random stream (distinct workers round independently)
+ *   index_base     global index of x[0]; a gradient cut into buckets gives the same codes as the
+ *                  whole when each bucket passes its offset
+ *   levels_out     device buffer in p->pack format
+ *   signplane_out  device uint32[ceil(d/32)] for the *_SIGNPLANE formats, else NULL */
+gq_status gq_quantize(const float *x, int64_t d, const float *norm, const gq_params *p /* host */,
+                      uint32_t worker, int64_t index_base,
+                      void *levels_out, uint32_t *signplane_out, void *hip_stream);
+
+/* Algorithm 1 line 9 on one device: A_j = sum over the K workers of the integer value of the code.
+ *   levels      host array of K device pointers to level buffers in p->pack format
+ *   signplanes  host array of K device pointers (the *_SIGNPLANE formats), else NULL
+ *   agg_out     device int32[d] or int16[d] according to p->agg
+ * Returns GQ_ERR_OVERFLOW (and enqueues nothing) if gq_check_width(p, K) fails. */
+gq_status gq_int_aggregate(const void *const *levels /* host */, const uint32_t *const *signplanes /* host */,
+                           int K, int64_t d, const gq_params *p /* host */, void *agg_out, void *hip_stream);
+
+/* Eq. (1): out_j = norm * A_j / (K*s) (linear) or norm * A_j / (K*2^(s-1)) (exponential): the MEAN
+ * of the workers' quantised gradients.
+ *   agg   device int32[d] or int16[d] according to p->agg
+ *   out   device fp32[d]; computed as fl32(fl32(A_j) * fl32(norm / (K*unit))) */
+gq_status gq_dequantize(const void *agg, int64_t d, const float *norm, const gq_params *p /* host */,
+                        int K, float *out, void *hip_stream);
+
+/* The fused call: gq_quantize for all K workers (worker word = position in x) and the integer sum,
+ * in registers, in one pass over the gradients.  Outputs are optional but at least one of agg_out
+ * and dequant_out must be given:
+ *   agg_out         device int32[d] / int16[d] (p->agg), or NULL
+ *   dequant_out     device fp32[d] as gq_dequantize would write it, or NULL
+ *   levels_out      host array of K device level buffers (p->pack) to also store the codes, or NULL
+ *   signplanes_out  host array of K device sign planes (the *_SIGNPLANE formats with levels_out), else NULL
+ * Results equal those of the separate calls bit for bit. */
+gq_status gq_fused_quantize_aggregate(const float *const *x /* host */, int K, int64_t d, const float *norm,
+                                      const gq_params *p /* host */, int64_t index_base,
+                                      void *agg_out, float *dequant_out,
+                                      void *const *levels_out /* host */, uint32_t *const *signplanes_out /* host */,
+                                      void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GQSGD_H */

@@ -1,0 +1,159 @@
+"""Thin ctypes binding of the C ABI in include/gqsgd.h.
+
+Argument marshalling only: every step of the path runs in the HIP kernels of libgqsgd.so.
+PyTorch is used for device memory (tensor.data_ptr()) and for the current HIP stream, nothing
+else.  There is no CPU fallback: if the library has not been built, importing this module raises.
+"""
+import ctypes as C
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libgqsgd.so")
+
+GQ_MAX_WORKERS = 64
+GQ_OK, GQ_ERR_INVALID_ARG, GQ_ERR_UNSUPPORTED, GQ_ERR_OVERFLOW, GQ_ERR_WORKSPACE, GQ_ERR_DEVICE = range(6)
+GQ_NORM_LINF, GQ_NORM_L2, GQ_NORM_L2_MAX = 0, 1, 2
+GQ_LINEAR, GQ_EXP = 0, 1
+GQ_PACK_I8, GQ_PACK_I4, GQ_PACK_U8_SIGNPLANE, GQ_PACK_U4_SIGNPLANE = 0, 1, 2, 3
+GQ_AGG_I32, GQ_AGG_I16 = 0, 1
+
+# every symbol include/gqsgd.h declares
+EXPORTS = ("gq_version", "gq_status_string", "gq_check_width", "gq_norm_workspace_bytes", "gq_global_norm",
+           "gq_quantize", "gq_int_aggregate", "gq_dequantize", "gq_fused_quantize_aggregate")
+
+
+class gq_params(C.Structure):
+    _fields_ = [("scheme", C.c_int32), ("s", C.c_int32), ("pack", C.c_int32), ("agg", C.c_int32),
+                ("seed", C.c_uint64)]
+
+
+class GQError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        name = _lib.gq_status_string(int(status)).decode() if _lib is not None else str(status)
+        super().__init__("%s failed: %s" % (where, name))
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("%s is missing: build it first (python -c 'import __graft_entry__ as g; g.build()' "
+                          "or python paper_2305_18627_amd/build.py); there is no fallback path" % LIB_PATH)
+    lib = C.CDLL(LIB_PATH)
+    vp, i64, u32, i32, sz = C.c_void_p, C.c_int64, C.c_uint32, C.c_int, C.c_size_t
+    pp = C.POINTER(gq_params)
+    sigs = {
+        "gq_version": (C.c_int, []),
+        "gq_status_string": (C.c_char_p, [i32]),
+        "gq_check_width": (i32, [pp, i32]),
+        "gq_norm_workspace_bytes": (sz, [i32, i64]),
+        "gq_global_norm": (i32, [C.POINTER(vp), i32, i64, i32, vp, vp, vp, sz, vp]),
+        "gq_quantize": (i32, [vp, i64, vp, pp, u32, i64, vp, vp, vp]),
+        "gq_int_aggregate": (i32, [C.POINTER(vp), C.POINTER(vp), i32, i64, pp, vp, vp]),
+        "gq_dequantize": (i32, [vp, i64, vp, pp, i32, vp, vp]),
+        "gq_fused_quantize_aggregate": (i32, [C.POINTER(vp), i32, i64, vp, pp, i64, vp, vp, C.POINTER(vp),
+                                               C.POINTER(vp), vp]),
+    }
+    for name, (res, args) in sigs.items():
+        f = getattr(lib, name)
+        f.restype = res
+        f.argtypes = args
+    return lib
+
+
+_lib = None
+_lib = _load()
+
+
+def lib():
+    """The loaded ctypes library (for tests that call the C ABI directly)."""
+    return _lib
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p(None)
+
+
+def _ptr_array(ts):
+    if ts is None:
+        return None
+    arr = (C.c_void_p * len(ts))(*[t.data_ptr() for t in ts])
+    return arr
+
+
+def _check(st, where):
+    if st != GQ_OK:
+        raise GQError(st, where)
+
+
+def make_params(scheme, s, pack=GQ_PACK_I8, agg=GQ_AGG_I32, seed=0):
+    return gq_params(int(scheme), int(s), int(pack), int(agg), int(seed))
+
+
+def levels_nbytes(d, pack):
+    return d if pack in (GQ_PACK_I8, GQ_PACK_U8_SIGNPLANE) else (d + 1) // 2
+
+
+def signplane_nwords(d):
+    return (d + 31) // 32
+
+
+def status_string(st):
+    return _lib.gq_status_string(int(st)).decode()
+
+
+def version():
+    return int(_lib.gq_version())
+
+
+def check_width(params, K):
+    """gq_check_width: the status code (GQ_OK / GQ_ERR_OVERFLOW / ...), not an exception."""
+    return int(_lib.gq_check_width(C.byref(params), int(K)))
+
+
+def norm_workspace_bytes(K, d):
+    return int(_lib.gq_norm_workspace_bytes(int(K), int(d)))
+
+
+def global_norm(xs, kind, norm_out, status_flags=None, workspace=None, stream=None):
+    """gq_global_norm over the K tensors xs (fp32, equal length).  Returns the workspace used."""
+    K, d = len(xs), (xs[0].numel() if xs else 0)
+    if workspace is None:
+        workspace = torch.empty(max(norm_workspace_bytes(K, d), 8), dtype=torch.uint8, device=norm_out.device)
+    st = _lib.gq_global_norm(_ptr_array(xs), K, d, int(kind), _ptr(norm_out), _ptr(status_flags),
+                             _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(st, "gq_global_norm")
+    return workspace
+
+
+def quantize(x, norm, params, worker, index_base, levels_out, signplane_out=None, stream=None):
+    st = _lib.gq_quantize(_ptr(x), x.numel(), _ptr(norm), C.byref(params), int(worker), int(index_base),
+                          _ptr(levels_out), _ptr(signplane_out), _stream(stream))
+    _check(st, "gq_quantize")
+
+
+def int_aggregate(levels, signplanes, d, params, agg_out, stream=None):
+    st = _lib.gq_int_aggregate(_ptr_array(levels), _ptr_array(signplanes), len(levels), int(d),
+                               C.byref(params), _ptr(agg_out), _stream(stream))
+    _check(st, "gq_int_aggregate")
+
+
+def dequantize(agg, d, norm, params, K, out, stream=None):
+    st = _lib.gq_dequantize(_ptr(agg), int(d), _ptr(norm), C.byref(params), int(K), _ptr(out), _stream(stream))
+    _check(st, "gq_dequantize")
+
+
+def fused_quantize_aggregate(xs, norm, params, index_base=0, agg_out=None, dequant_out=None,
+                             levels_out=None, signplanes_out=None, stream=None):
+    K, d = len(xs), (xs[0].numel() if xs else 0)
+    st = _lib.gq_fused_quantize_aggregate(_ptr_array(xs), K, d, _ptr(norm), C.byref(params), int(index_base),
+                                          _ptr(agg_out), _ptr(dequant_out), _ptr_array(levels_out),
+                                          _ptr_array(signplanes_out), _stream(stream))
+    _check(st, "gq_fused_quantize_aggregate")

@@ -1,0 +1,158 @@
+// Device-side building blocks of the Global-QSGD hot path for gfx950 (wave64).
+// Internal to the library; the public surface is include/gqsgd.h.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gq {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kBlock = 256;          // threads per workgroup: four wave64
+constexpr int kMaxWorkers = 64;
+
+// ---------------------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11).  The 32x32->64 products map to v_mad_u64_u32; the key
+// schedule depends on the seed only and stays in scalar registers.
+// ---------------------------------------------------------------------------------------------
+struct Words4 { uint32_t w[4]; };
+
+__device__ __forceinline__ Words4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                uint32_t k0, uint32_t k1)
+{
+#pragma unroll
+    for (int r = 0; r < 10; r++) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    Words4 o;
+    o.w[0] = c0; o.w[1] = c1; o.w[2] = c2; o.w[3] = c3;
+    return o;
+}
+
+// The four random words of the coordinates 4*call .. 4*call+3 of one worker (Eq. (2) draws).
+__device__ __forceinline__ Words4 random_words(uint64_t seed, uint32_t worker, uint64_t call)
+{
+    return philox4x32_10((uint32_t)call, (uint32_t)(call >> 32), worker, 0u,
+                         (uint32_t)seed, (uint32_t)(seed >> 32));
+}
+
+// ---------------------------------------------------------------------------------------------
+// Per-call constants derived from the norm on the device (Algorithm 1 line 3, y = |x| / norm).
+// ---------------------------------------------------------------------------------------------
+struct Scale {
+    float scale;   // s / norm (linear) or 2^(s-1) / norm (exponential); 0 if the norm is unusable
+    float top;     // s (linear) or 2^(s-1) (exponential) as a float
+};
+
+template <int SCHEME>
+__device__ __forceinline__ Scale make_scale(float norm, int s)
+{
+    Scale sc;
+    sc.top = SCHEME == 0 ? (float)s : __uint_as_float((uint32_t)(127 + s - 1) << 23);
+    const float q = sc.top / norm;                          // correctly rounded division
+    const bool ok = (norm > 0.0f) && (q <= 3.402823466e+38f);
+    sc.scale = ok ? q : 0.0f;                               // zero / non-finite norm => every code is 0
+    return sc;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Definition 1 / Eq. (2) for one coordinate.  Both return the signed level as a float whose
+// integer conversion is exact; `value` is what is added to the sum, `code` what is stored.
+// ---------------------------------------------------------------------------------------------
+template <int SCHEME> struct Round;
+
+// Linear grid l_u = (s-u)/s: t = y*s lies between h and h+1; the upper one is taken iff U' < t-h.
+template <> struct Round<0> {
+    static __device__ __forceinline__ float value(float x, const Scale &sc, uint32_t r)
+    {
+        const float u = (float)r * 0x1.fffffep-33f;                       // U' in [0,1)
+        const float v = __builtin_fmaf(__builtin_fabsf(x), sc.scale, -u); // t - U', one rounding
+        const float c = __builtin_fminf(__builtin_ceilf(v), sc.top);      // clamp at the top level
+        return __builtin_copysignf(c, x);
+    }
+    static __device__ __forceinline__ int code_of_value(float value) { return (int)value; }
+};
+
+// Exponential grid {0} u {2^-j}: z = y*2^(s-1); a binary32 z >= 1 is rounded to a neighbouring power of
+// two by adding 23 random bits to its mantissa; z < 1 is first moved to 1+z in [1,2).
+template <> struct Round<1> {
+    static __device__ __forceinline__ float value(float x, const Scale &sc, uint32_t r)
+    {
+        const float z = __builtin_fminf(__builtin_fabsf(x) * sc.scale, sc.top);
+        const float one = z < 1.0f ? 1.0f : 0.0f;
+        const float w = z + one;
+        const uint32_t b = __float_as_uint(w) + (r >> 9);
+        const float p2 = __uint_as_float(b & 0x7F800000u) - one;          // 0, 1, 2, 4, ..
+        return __builtin_copysignf(p2, x);
+    }
+    // value = +-2^(k-1) or 0  ->  code = +-k or 0
+    static __device__ __forceinline__ int code_of_value(float value)
+    {
+        const uint32_t b = __float_as_uint(value);
+        const int k = max((int)((b >> 23) & 0xFFu) - 126, 0);
+        return (b >> 31) ? -k : k;
+    }
+};
+
+// ---------------------------------------------------------------------------------------------
+// Wave reductions for the norm: DPP inside a row of 16 lanes (quad permutes, then the two mirror
+// patterns), ds_swizzle across the two rows of a half wave, readlane across the halves.
+// Every lane of the wave must be active.  The result is uniform.
+// ---------------------------------------------------------------------------------------------
+template <int CTRL> __device__ __forceinline__ uint32_t dpp32(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, false);
+}
+template <int CTRL> __device__ __forceinline__ double dpp64(double v)
+{
+    const uint64_t b = (uint64_t)__double_as_longlong(v);
+    const uint32_t lo = dpp32<CTRL>((uint32_t)b), hi = dpp32<CTRL>((uint32_t)(b >> 32));
+    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+__device__ __forceinline__ uint32_t swizzle_xor16(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, 0x401F);   // bit-mask mode: lane ^ 16
+}
+constexpr int kDppQuadXor1 = 0xB1;     // quad_perm:[1,0,3,2]
+constexpr int kDppQuadXor2 = 0x4E;     // quad_perm:[2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;  // row_half_mirror: lane i <-> 7-i of each 8
+constexpr int kDppMirror = 0x140;      // row_mirror:      lane i <-> 15-i of each 16
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+    v += dpp64<kDppQuadXor1>(v);
+    v += dpp64<kDppQuadXor2>(v);
+    v += dpp64<kDppHalfMirror>(v);
+    v += dpp64<kDppMirror>(v);
+    const uint64_t b = (uint64_t)__double_as_longlong(v);
+    const uint32_t lo = swizzle_xor16((uint32_t)b), hi = swizzle_xor16((uint32_t)(b >> 32));
+    v += __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+    const uint64_t t = (uint64_t)__double_as_longlong(v);
+    const uint32_t lo0 = __builtin_amdgcn_readlane((int)(uint32_t)t, 0), hi0 = __builtin_amdgcn_readlane((int)(uint32_t)(t >> 32), 0);
+    const uint32_t lo1 = __builtin_amdgcn_readlane((int)(uint32_t)t, 32), hi1 = __builtin_amdgcn_readlane((int)(uint32_t)(t >> 32), 32);
+    return __longlong_as_double((long long)(((uint64_t)hi0 << 32) | lo0)) +
+           __longlong_as_double((long long)(((uint64_t)hi1 << 32) | lo1));
+}
+__device__ __forceinline__ uint32_t wave_max(uint32_t v)
+{
+    v = max(v, dpp32<kDppQuadXor1>(v));
+    v = max(v, dpp32<kDppQuadXor2>(v));
+    v = max(v, dpp32<kDppHalfMirror>(v));
+    v = max(v, dpp32<kDppMirror>(v));
+    v = max(v, swizzle_xor16(v));
+    return max((uint32_t)__builtin_amdgcn_readlane((int)v, 0), (uint32_t)__builtin_amdgcn_readlane((int)v, 32));
+}
+
+}  // namespace gq

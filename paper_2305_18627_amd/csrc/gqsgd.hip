@@ -1,0 +1,651 @@
+// Kernels and C entry points of the Global-QSGD hot path for MI355X (gfx950).
+// The contract of every entry point is stated in include/gqsgd.h.
+//
+// Data layout.  Every buffer is a flat array in HBM.  A lane always owns four consecutive
+// coordinates of a gradient (one 128-bit load per worker), which are also the four words of one
+// Philox call, so that a wave reads 1 KiB of contiguous gradient per worker and load.  All traffic is
+// streaming with no reuse: nothing is staged through LDS except the few words of the reductions.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "gqsgd.h"
+#include "gq_device.hpp"
+
+namespace gq {
+
+struct GradPtrs { const float *x[kMaxWorkers]; };
+struct LevelPtrs { void *lv[kMaxWorkers]; uint32_t *sp[kMaxWorkers]; };
+struct LevelCPtrs { const void *lv[kMaxWorkers]; const uint32_t *sp[kMaxWorkers]; };
+
+// =============================================================================================
+// Algorithm 1 line 1: global norm.  Pass 1: every block reduces a strided share of one worker's
+// gradient to one 8-byte partial (a uint32 bit pattern for the max norm, a binary64 sum of squares
+// otherwise).  Pass 2: one block folds the partials, per worker and then across workers, in a
+// fixed order, and writes the norm and the status word.  No atomics: the result is reproducible.
+// =============================================================================================
+constexpr int kNormVecPerThread = 8;     // target number of 128-bit loads per thread
+constexpr int kNormMaxBlocksPerWorker = 1024;
+
+static inline int norm_blocks_per_worker(int64_t d)
+{
+    const int64_t nvec = d / 4;
+    int64_t b = (nvec + (int64_t)kBlock * kNormVecPerThread - 1) / ((int64_t)kBlock * kNormVecPerThread);
+    if (b < 1) b = 1;
+    if (b > kNormMaxBlocksPerWorker) b = kNormMaxBlocksPerWorker;
+    return (int)b;
+}
+
+__device__ __forceinline__ uint32_t abs_bits(float v) { return __float_as_uint(v) & 0x7FFFFFFFu; }
+
+template <bool MAXNORM>
+__global__ void __launch_bounds__(kBlock) norm_partial_kernel(GradPtrs P, int64_t d, int bpw, uint64_t *partial)
+{
+    const int worker = blockIdx.x / bpw;
+    const int blk = blockIdx.x - worker * bpw;
+    const float *x = P.x[worker];
+    const f32x4 *xv = reinterpret_cast<const f32x4 *>(x);
+    const int64_t nvec = d >> 2;
+    const int64_t step = (int64_t)bpw * kBlock;
+    int64_t v = (int64_t)blk * kBlock + threadIdx.x;
+
+    uint32_t m0 = 0, m1 = 0, m2 = 0, m3 = 0;
+    double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+    auto take = [&](const f32x4 &a) {
+        if (MAXNORM) {
+            // |x| compared as unsigned bit patterns: ordered like the values, NaN above Inf above finite
+            m0 = max(m0, abs_bits(a.x)); m1 = max(m1, abs_bits(a.y));
+            m2 = max(m2, abs_bits(a.z)); m3 = max(m3, abs_bits(a.w));
+        } else {
+            const double x0 = a.x, x1 = a.y, x2 = a.z, x3 = a.w;   // squares are exact in binary64
+            a0 = __builtin_fma(x0, x0, a0); a1 = __builtin_fma(x1, x1, a1);
+            a2 = __builtin_fma(x2, x2, a2); a3 = __builtin_fma(x3, x3, a3);
+        }
+    };
+    for (; v + 3 * step < nvec; v += 4 * step) {
+        const f32x4 b0 = __builtin_nontemporal_load(xv + v);
+        const f32x4 b1 = __builtin_nontemporal_load(xv + v + step);
+        const f32x4 b2 = __builtin_nontemporal_load(xv + v + 2 * step);
+        const f32x4 b3 = __builtin_nontemporal_load(xv + v + 3 * step);
+        take(b0); take(b1); take(b2); take(b3);
+    }
+    for (; v < nvec; v += step) take(__builtin_nontemporal_load(xv + v));
+    if (blk == 0 && (int64_t)threadIdx.x < (d & 3)) {            // ragged tail: up to three coordinates
+        const float t = x[(nvec << 2) + threadIdx.x];
+        f32x4 a = {t, 0.0f, 0.0f, 0.0f};
+        take(a);
+    }
+
+    __shared__ uint64_t sh[kBlock / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint64_t mine;
+    if (MAXNORM) mine = wave_max(max(max(m0, m1), max(m2, m3)));
+    else         mine = (uint64_t)__double_as_longlong(wave_sum((a0 + a1) + (a2 + a3)));
+    if (lane == 0) sh[wave] = mine;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint64_t r = sh[0];
+        for (int i = 1; i < kBlock / 64; i++) {
+            if (MAXNORM) r = max(r, sh[i]);
+            else r = (uint64_t)__double_as_longlong(__longlong_as_double((long long)r) + __longlong_as_double((long long)sh[i]));
+        }
+        partial[blockIdx.x] = r;
+    }
+}
+
+// kind: 0 = (inf,inf), 1 = (2,2), 2 = (2,inf)
+__global__ void __launch_bounds__(kBlock) norm_final_kernel(const uint64_t *partial, int K, int bpw, int kind,
+                                                            float *norm_out, uint32_t *status_flags)
+{
+    __shared__ uint64_t sh[kBlock / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t maxbits = 0;        // kind 0
+    double total = 0.0;          // kind 1: sum over workers; kind 2: max over workers
+    for (int w = 0; w < K; w++) {
+        uint32_t m = 0;
+        double a = 0.0;
+        for (int i = threadIdx.x; i < bpw; i += kBlock) {
+            const uint64_t p = partial[(int64_t)w * bpw + i];
+            if (kind == 0) m = max(m, (uint32_t)p);
+            else a += __longlong_as_double((long long)p);
+        }
+        uint64_t mine = kind == 0 ? (uint64_t)wave_max(m) : (uint64_t)__double_as_longlong(wave_sum(a));
+        __syncthreads();
+        if (lane == 0) sh[wave] = mine;
+        __syncthreads();
+        if (kind == 0) {
+            for (int i = 0; i < kBlock / 64; i++) maxbits = max(maxbits, (uint32_t)sh[i]);
+        } else {
+            double sw = 0.0;
+            for (int i = 0; i < kBlock / 64; i++) sw += __longlong_as_double((long long)sh[i]);
+            if (kind == 1) total += sw;
+            else total = (sw != sw || total != total) ? (sw + total) : (sw > total ? sw : total);  // NaN is sticky
+        }
+    }
+    if (threadIdx.x == 0) {
+        const float n = kind == 0 ? __uint_as_float(maxbits) : (float)__builtin_sqrt(total);
+        *norm_out = n;
+        if (status_flags) {
+            uint32_t f = 0;
+            if (!(__builtin_fabsf(n) <= 3.402823466e+38f)) f |= 1u;
+            if (n == 0.0f) f |= 2u;
+            *status_flags = f;
+        }
+    }
+}
+
+// =============================================================================================
+// Algorithm 1 lines 2-5 and 9 fused: quantize the K workers' coordinates in registers, add the
+// integer values, write the sum (and/or its dequantised mean, Eq. (1), and/or the packed codes).
+//   SCHEME  0 linear, 1 exponential
+//   KT      compile-time worker count (fully unrolled, K loads in flight), 0 = run-time K
+//   LEVELS  also store every worker's packed codes
+// =============================================================================================
+__device__ __forceinline__ f32x4 load_coords(const float *x, int64_t v, int nvalid)
+{
+    if (nvalid == 4) return __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(x) + v);
+    f32x4 a = {0.0f, 0.0f, 0.0f, 0.0f};
+    const float *t = x + (v << 2);
+    if (nvalid > 0) a.x = t[0];
+    if (nvalid > 1) a.y = t[1];
+    if (nvalid > 2) a.z = t[2];
+    return a;
+}
+
+// OR over the 8 lanes that share one 32-bit sign word.  Every lane of the wave must be active.
+__device__ __forceinline__ uint32_t or_over_8_lanes(uint32_t v)
+{
+    v |= dpp32<kDppQuadXor1>(v);
+    v |= dpp32<kDppQuadXor2>(v);
+    v |= dpp32<kDppHalfMirror>(v);
+    return v;
+}
+
+__device__ __forceinline__ void store_codes(void *lv, uint32_t *sp, int pack, int64_t v, int nvalid, int64_t d,
+                                            int q0, int q1, int q2, int q3)
+{
+    const bool plane = pack >= 2;
+    if (plane) {
+        const uint32_t nib = (uint32_t)(q0 < 0) | ((uint32_t)(q1 < 0) << 1) | ((uint32_t)(q2 < 0) << 2) |
+                             ((uint32_t)(q3 < 0) << 3);
+        const uint32_t word = or_over_8_lanes(nib << (4 * (threadIdx.x & 7)));
+        if ((threadIdx.x & 7) == 0 && ((v & ~(int64_t)7) << 2) < d) sp[v >> 3] = word;
+        q0 = abs(q0); q1 = abs(q1); q2 = abs(q2); q3 = abs(q3);
+    }
+    if (nvalid == 0) return;
+    if (pack == GQ_PACK_I8 || pack == GQ_PACK_U8_SIGNPLANE) {
+        const uint32_t w = (uint32_t)(q0 & 255) | ((uint32_t)(q1 & 255) << 8) | ((uint32_t)(q2 & 255) << 16) |
+                           ((uint32_t)(q3 & 255) << 24);
+        if (nvalid == 4) {
+            __builtin_nontemporal_store(w, reinterpret_cast<uint32_t *>(lv) + v);
+        } else {
+            uint8_t *b = reinterpret_cast<uint8_t *>(lv) + (v << 2);
+            for (int i = 0; i < nvalid; i++) b[i] = (uint8_t)(w >> (8 * i));
+        }
+    } else {
+        const uint32_t w = (uint32_t)(q0 & 15) | ((uint32_t)(q1 & 15) << 4) | ((uint32_t)(q2 & 15) << 8) |
+                           ((uint32_t)(q3 & 15) << 12);
+        if (nvalid == 4) {
+            __builtin_nontemporal_store((uint16_t)w, reinterpret_cast<uint16_t *>(lv) + v);
+        } else {
+            uint8_t *b = reinterpret_cast<uint8_t *>(lv) + (v << 1);
+            b[0] = (uint8_t)w;
+            if (nvalid == 3) b[1] = (uint8_t)(w >> 8);
+        }
+    }
+}
+
+template <int SCHEME, int KT, bool LEVELS>
+__global__ void __launch_bounds__(kBlock)
+quantize_aggregate_kernel(GradPtrs P, LevelPtrs L, int K, int64_t d, const float *__restrict__ norm, int s,
+                          uint64_t seed, uint32_t worker0, uint64_t call_base, int pack,
+                          void *__restrict__ agg_out, int agg_fmt, float *__restrict__ deq_out, float deq_div)
+{
+    const int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t nfull = d >> 2;
+    const int nvalid = v < nfull ? 4 : (v == nfull ? (int)(d & 3) : 0);
+    if (!LEVELS && nvalid == 0) return;          // with LEVELS the sign-plane exchange needs whole waves
+
+    const float nrm = *norm;
+    const Scale sc = make_scale<SCHEME>(nrm, s);
+    const uint64_t call = call_base + (uint64_t)v;
+    const int Kc = KT > 0 ? KT : K;
+
+    int a0 = 0, a1 = 0, a2 = 0, a3 = 0;
+    auto one_worker = [&](int w, const f32x4 &g) {
+        const Words4 r = random_words(seed, worker0 + (uint32_t)w, call);
+        const float f0 = Round<SCHEME>::value(g.x, sc, r.w[0]);
+        const float f1 = Round<SCHEME>::value(g.y, sc, r.w[1]);
+        const float f2 = Round<SCHEME>::value(g.z, sc, r.w[2]);
+        const float f3 = Round<SCHEME>::value(g.w, sc, r.w[3]);
+        a0 += (int)f0; a1 += (int)f1; a2 += (int)f2; a3 += (int)f3;
+        if (LEVELS) {
+            store_codes(L.lv[w], L.sp[w], pack, v, nvalid, d, Round<SCHEME>::code_of_value(f0),
+                        Round<SCHEME>::code_of_value(f1), Round<SCHEME>::code_of_value(f2),
+                        Round<SCHEME>::code_of_value(f3));
+        }
+    };
+    if (KT > 0) {
+        f32x4 g[KT > 0 ? KT : 1];
+#pragma unroll
+        for (int w = 0; w < KT; w++) g[w] = load_coords(P.x[w], v, nvalid);
+#pragma unroll
+        for (int w = 0; w < KT; w++) one_worker(w, g[w]);
+    } else {
+        int w = 0;
+        for (; w + 4 <= Kc; w += 4) {
+            const f32x4 g0 = load_coords(P.x[w], v, nvalid), g1 = load_coords(P.x[w + 1], v, nvalid);
+            const f32x4 g2 = load_coords(P.x[w + 2], v, nvalid), g3 = load_coords(P.x[w + 3], v, nvalid);
+            one_worker(w, g0); one_worker(w + 1, g1); one_worker(w + 2, g2); one_worker(w + 3, g3);
+        }
+        for (; w < Kc; w++) one_worker(w, load_coords(P.x[w], v, nvalid));
+    }
+    if (nvalid == 0) return;
+
+    if (agg_out) {
+        if (agg_fmt == GQ_AGG_I32) {
+            if (nvalid == 4) {
+                const i32x4 o = {a0, a1, a2, a3};
+                __builtin_nontemporal_store(o, reinterpret_cast<i32x4 *>(agg_out) + v);
+            } else {
+                int *o = reinterpret_cast<int *>(agg_out) + (v << 2);
+                o[0] = a0;
+                if (nvalid > 1) o[1] = a1;
+                if (nvalid > 2) o[2] = a2;
+            }
+        } else {
+            if (nvalid == 4) {
+                const i16x4 o = {(short)a0, (short)a1, (short)a2, (short)a3};
+                __builtin_nontemporal_store(o, reinterpret_cast<i16x4 *>(agg_out) + v);
+            } else {
+                short *o = reinterpret_cast<short *>(agg_out) + (v << 2);
+                o[0] = (short)a0;
+                if (nvalid > 1) o[1] = (short)a1;
+                if (nvalid > 2) o[2] = (short)a2;
+            }
+        }
+    }
+    if (deq_out) {
+        const float c = sc.scale != 0.0f ? nrm / deq_div : 0.0f;     // Eq. (1): norm / (n * unit)
+        if (nvalid == 4) {
+            const f32x4 o = {(float)a0 * c, (float)a1 * c, (float)a2 * c, (float)a3 * c};
+            __builtin_nontemporal_store(o, reinterpret_cast<f32x4 *>(deq_out) + v);
+        } else {
+            float *o = deq_out + (v << 2);
+            o[0] = (float)a0 * c;
+            if (nvalid > 1) o[1] = (float)a1 * c;
+            if (nvalid > 2) o[2] = (float)a2 * c;
+        }
+    }
+}
+
+// =============================================================================================
+// Algorithm 1 line 9 on stored codes: a lane owns 16 bytes of every worker's level buffer
+// (16 coordinates at 8 bits, 32 at 4 bits), widens, adds, and writes int32 or int16 sums.
+// =============================================================================================
+template <int SCHEME, int PACK>
+__global__ void __launch_bounds__(kBlock)
+int_aggregate_kernel(LevelCPtrs L, int K, int64_t d, void *__restrict__ agg_out, int agg_fmt)
+{
+    constexpr bool kNibble = (PACK == GQ_PACK_I4 || PACK == GQ_PACK_U4_SIGNPLANE);
+    constexpr bool kPlane = (PACK == GQ_PACK_U8_SIGNPLANE || PACK == GQ_PACK_U4_SIGNPLANE);
+    constexpr int kCoords = kNibble ? 32 : 16;
+    const int64_t u = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t c0 = u * kCoords;
+    if (c0 >= d) return;
+    const int nvalid = (int)min((int64_t)kCoords, d - c0);
+    const int64_t total_bytes = kNibble ? (d + 1) / 2 : d;
+    const int nbytes = (int)min((int64_t)16, total_bytes - (u << 4));
+
+    int acc[kCoords];
+#pragma unroll
+    for (int i = 0; i < kCoords; i++) acc[i] = 0;
+
+    for (int w = 0; w < K; w++) {
+        u32x4 data;
+        if (nbytes == 16) {
+            data = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(L.lv[w]) + u);
+        } else {
+            const uint8_t *b = reinterpret_cast<const uint8_t *>(L.lv[w]) + (u << 4);
+            uint32_t t[4] = {0u, 0u, 0u, 0u};
+            for (int i = 0; i < nbytes; i++) t[i >> 2] |= (uint32_t)b[i] << (8 * (i & 3));
+            data.x = t[0]; data.y = t[1]; data.z = t[2]; data.w = t[3];
+        }
+        uint32_t signs = 0;
+        if (kPlane) {
+            const uint32_t word = L.sp[w][c0 >> 5];
+            signs = kNibble ? word : ((word >> (16 * (int)(u & 1))) & 0xFFFFu);
+        }
+        const uint32_t dw[4] = {data.x, data.y, data.z, data.w};
+#pragma unroll
+        for (int i = 0; i < kCoords; i++) {
+            const uint32_t word = dw[kNibble ? i >> 3 : i >> 2];
+            int q;
+            if (PACK == GQ_PACK_I8)      q = (int)(int8_t)(word >> (8 * (i & 3)));
+            else if (PACK == GQ_PACK_I4) q = ((int)(word << (28 - 4 * (i & 7)))) >> 28;
+            else if (PACK == GQ_PACK_U8_SIGNPLANE) q = (int)((word >> (8 * (i & 3))) & 255u);
+            else                         q = (int)((word >> (4 * (i & 7))) & 15u);
+            int val;
+            if (SCHEME == 0) {
+                val = q;
+                if (kPlane) val = ((signs >> i) & 1u) ? -q : q;
+            } else {
+                const bool neg = kPlane ? (((signs >> i) & 1u) != 0u) : (q < 0);
+                const int mag = (int)((1u << abs(q)) >> 1);          // 2^(k-1), 0 for k = 0
+                val = neg ? -mag : mag;
+            }
+            acc[i] += val;
+        }
+    }
+
+    if (agg_fmt == GQ_AGG_I32) {
+        int *o = reinterpret_cast<int *>(agg_out) + c0;
+        if (nvalid == kCoords) {
+#pragma unroll
+            for (int i = 0; i < kCoords; i += 4) {
+                const i32x4 t = {acc[i], acc[i + 1], acc[i + 2], acc[i + 3]};
+                __builtin_nontemporal_store(t, reinterpret_cast<i32x4 *>(o + i));
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < kCoords; i++) if (i < nvalid) o[i] = acc[i];
+        }
+    } else {
+        short *o = reinterpret_cast<short *>(agg_out) + c0;
+        if (nvalid == kCoords) {
+#pragma unroll
+            for (int i = 0; i < kCoords; i += 8) {
+                const u32x4 t = {((uint32_t)acc[i] & 0xFFFFu) | ((uint32_t)acc[i + 1] << 16),
+                                 ((uint32_t)acc[i + 2] & 0xFFFFu) | ((uint32_t)acc[i + 3] << 16),
+                                 ((uint32_t)acc[i + 4] & 0xFFFFu) | ((uint32_t)acc[i + 5] << 16),
+                                 ((uint32_t)acc[i + 6] & 0xFFFFu) | ((uint32_t)acc[i + 7] << 16)};
+                __builtin_nontemporal_store(t, reinterpret_cast<u32x4 *>(o + i));
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < kCoords; i++) if (i < nvalid) o[i] = (short)acc[i];
+        }
+    }
+}
+
+// =============================================================================================
+// Eq. (1): out = norm * A / (n * unit).
+// =============================================================================================
+template <typename T>
+__global__ void __launch_bounds__(kBlock)
+dequantize_kernel(const T *__restrict__ agg, int64_t d, const float *__restrict__ norm, float deq_div,
+                  float *__restrict__ out)
+{
+    typedef T tx4 __attribute__((ext_vector_type(4)));
+    const int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t nfull = d >> 2;
+    const int nvalid = v < nfull ? 4 : (v == nfull ? (int)(d & 3) : 0);
+    if (nvalid == 0) return;
+    const float nrm = *norm;
+    const float c = (nrm > 0.0f && nrm <= 3.402823466e+38f) ? nrm / deq_div : 0.0f;
+    if (nvalid == 4) {
+        const tx4 a = __builtin_nontemporal_load(reinterpret_cast<const tx4 *>(agg) + v);
+        const f32x4 o = {(float)a.x * c, (float)a.y * c, (float)a.z * c, (float)a.w * c};
+        __builtin_nontemporal_store(o, reinterpret_cast<f32x4 *>(out) + v);
+    } else {
+        for (int i = 0; i < nvalid; i++) out[(v << 2) + i] = (float)agg[(v << 2) + i] * c;
+    }
+}
+
+// =============================================================================================
+// Host side: argument checks and launches.
+// =============================================================================================
+static inline bool aligned(const void *p, size_t a) { return p != nullptr && ((uintptr_t)p % a) == 0; }
+
+static gq_status check_params(const gq_params *p, bool uses_pack, bool uses_agg)
+{
+    if (!p) return GQ_ERR_INVALID_ARG;
+    if (p->scheme != GQ_LINEAR && p->scheme != GQ_EXP) return GQ_ERR_INVALID_ARG;
+    if (p->s < 1) return GQ_ERR_INVALID_ARG;
+    if (p->scheme == GQ_LINEAR && p->s > 32767) return GQ_ERR_UNSUPPORTED;
+    if (p->scheme == GQ_EXP && p->s > 31) return GQ_ERR_UNSUPPORTED;
+    if (uses_pack) {
+        if (p->pack < GQ_PACK_I8 || p->pack > GQ_PACK_U4_SIGNPLANE) return GQ_ERR_INVALID_ARG;
+        const int lim = p->pack == GQ_PACK_I8 ? 127 : p->pack == GQ_PACK_I4 ? 7 : p->pack == GQ_PACK_U8_SIGNPLANE ? 255 : 15;
+        if (p->s > lim) return GQ_ERR_UNSUPPORTED;
+    }
+    if (uses_agg && p->agg != GQ_AGG_I32 && p->agg != GQ_AGG_I16) return GQ_ERR_INVALID_ARG;
+    return GQ_OK;
+}
+
+static int64_t max_aggregate(const gq_params *p, int K)
+{
+    return p->scheme == GQ_LINEAR ? (int64_t)K * p->s : (int64_t)K * ((int64_t)1 << (p->s - 1));
+}
+
+static float dequant_divisor(const gq_params *p, int K)
+{
+    // n * (1/unit): K*s or K*2^(s-1); both are exact in binary32 for the supported ranges
+    return p->scheme == GQ_LINEAR ? (float)((int64_t)K * p->s) : (float)K * (float)((int64_t)1 << (p->s - 1));
+}
+
+static inline gq_status launched()
+{
+    return hipGetLastError() == hipSuccess ? GQ_OK : GQ_ERR_DEVICE;
+}
+
+static inline bool grid_fits(int64_t blocks) { return blocks >= 0 && blocks <= 0x7FFFFFFF; }
+
+template <int SCHEME>
+static gq_status launch_quantize_aggregate(const GradPtrs &P, const LevelPtrs &L, bool levels, int K, int64_t d,
+                                           const float *norm, const gq_params *p, uint32_t worker0,
+                                           int64_t index_base, void *agg_out, float *deq_out, hipStream_t st)
+{
+    const int64_t nvec = (d + 3) / 4;
+    const int64_t blocks = (nvec + kBlock - 1) / kBlock;
+    if (!grid_fits(blocks)) return GQ_ERR_INVALID_ARG;
+    const dim3 grid((unsigned)blocks), block(kBlock);
+    const uint64_t call_base = (uint64_t)index_base / 4u;
+    const float div = dequant_divisor(p, K);
+#define GQ_LAUNCH(KT, LV)                                                                                  \
+    hipLaunchKernelGGL((quantize_aggregate_kernel<SCHEME, KT, LV>), grid, block, 0, st, P, L, K, d, norm,  \
+                       p->s, p->seed, worker0, call_base, p->pack, agg_out, p->agg, deq_out, div)
+    if (levels) GQ_LAUNCH(0, true);
+    else if (K == 4) GQ_LAUNCH(4, false);
+    else if (K == 8) GQ_LAUNCH(8, false);
+    else if (K == 16) GQ_LAUNCH(16, false);
+    else if (K == 32) GQ_LAUNCH(32, false);
+    else GQ_LAUNCH(0, false);
+#undef GQ_LAUNCH
+    return launched();
+}
+
+}  // namespace gq
+
+using namespace gq;
+
+extern "C" {
+
+int gq_version(void) { return 1000; }
+
+const char *gq_status_string(gq_status st)
+{
+    switch (st) {
+    case GQ_OK: return "GQ_OK";
+    case GQ_ERR_INVALID_ARG: return "GQ_ERR_INVALID_ARG";
+    case GQ_ERR_UNSUPPORTED: return "GQ_ERR_UNSUPPORTED";
+    case GQ_ERR_OVERFLOW: return "GQ_ERR_OVERFLOW";
+    case GQ_ERR_WORKSPACE: return "GQ_ERR_WORKSPACE";
+    case GQ_ERR_DEVICE: return "GQ_ERR_DEVICE";
+    }
+    return "GQ_ERR_UNKNOWN";
+}
+
+gq_status gq_check_width(const gq_params *p, int K)
+{
+    const gq_status st = check_params(p, false, true);
+    if (st != GQ_OK) return st;
+    if (K < 1 || K > GQ_MAX_WORKERS) return GQ_ERR_INVALID_ARG;
+    const int64_t lim = p->agg == GQ_AGG_I32 ? 2147483647LL : 32767LL;
+    return max_aggregate(p, K) <= lim ? GQ_OK : GQ_ERR_OVERFLOW;
+}
+
+size_t gq_norm_workspace_bytes(int K, int64_t d)
+{
+    if (K < 1 || K > GQ_MAX_WORKERS || d < 0) return 0;
+    return (size_t)K * (size_t)norm_blocks_per_worker(d) * sizeof(uint64_t);
+}
+
+gq_status gq_global_norm(const float *const *x, int K, int64_t d, gq_norm_kind kind, float *norm_out,
+                         uint32_t *status_flags, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!x || K < 1 || K > GQ_MAX_WORKERS || d < 0) return GQ_ERR_INVALID_ARG;
+    if (kind != GQ_NORM_LINF && kind != GQ_NORM_L2 && kind != GQ_NORM_L2_MAX) return GQ_ERR_INVALID_ARG;
+    if (!aligned(norm_out, 4) || (status_flags && !aligned(status_flags, 4))) return GQ_ERR_INVALID_ARG;
+    GradPtrs P;
+    for (int i = 0; i < K; i++) {
+        if (d > 0 && !aligned(x[i], 16)) return GQ_ERR_INVALID_ARG;
+        P.x[i] = x[i];
+    }
+    if (!workspace || workspace_bytes < gq_norm_workspace_bytes(K, d)) return GQ_ERR_WORKSPACE;
+    if (!aligned(workspace, 8)) return GQ_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int bpw = d > 0 ? norm_blocks_per_worker(d) : 0;
+    uint64_t *partial = reinterpret_cast<uint64_t *>(workspace);
+    if (bpw > 0) {
+        const dim3 grid((unsigned)(K * bpw)), block(kBlock);
+        if (kind == GQ_NORM_LINF) hipLaunchKernelGGL(norm_partial_kernel<true>, grid, block, 0, st, P, d, bpw, partial);
+        else hipLaunchKernelGGL(norm_partial_kernel<false>, grid, block, 0, st, P, d, bpw, partial);
+        if (launched() != GQ_OK) return GQ_ERR_DEVICE;
+    }
+    hipLaunchKernelGGL(norm_final_kernel, dim3(1), dim3(kBlock), 0, st, partial, K, bpw, (int)kind, norm_out, status_flags);
+    return launched();
+}
+
+gq_status gq_quantize(const float *x, int64_t d, const float *norm, const gq_params *p, uint32_t worker,
+                      int64_t index_base, void *levels_out, uint32_t *signplane_out, void *hip_stream)
+{
+    const gq_status st = check_params(p, true, false);
+    if (st != GQ_OK) return st;
+    if (d < 0 || index_base < 0 || (index_base & 3) != 0) return GQ_ERR_INVALID_ARG;
+    if (!aligned(norm, 4)) return GQ_ERR_INVALID_ARG;
+    const bool plane = p->pack >= GQ_PACK_U8_SIGNPLANE;
+    if (d > 0 && (!aligned(x, 16) || !aligned(levels_out, 16))) return GQ_ERR_INVALID_ARG;
+    if (d > 0 && plane && !aligned(signplane_out, 4)) return GQ_ERR_INVALID_ARG;
+    if (d == 0) return GQ_OK;
+    GradPtrs P;
+    LevelPtrs L;
+    P.x[0] = x;
+    L.lv[0] = levels_out;
+    L.sp[0] = plane ? signplane_out : nullptr;
+    gq_params q = *p;
+    q.agg = GQ_AGG_I32;
+    if (p->scheme == GQ_LINEAR)
+        return launch_quantize_aggregate<0>(P, L, true, 1, d, norm, &q, worker, index_base, nullptr, nullptr, (hipStream_t)hip_stream);
+    return launch_quantize_aggregate<1>(P, L, true, 1, d, norm, &q, worker, index_base, nullptr, nullptr, (hipStream_t)hip_stream);
+}
+
+gq_status gq_fused_quantize_aggregate(const float *const *x, int K, int64_t d, const float *norm, const gq_params *p,
+                                      int64_t index_base, void *agg_out, float *dequant_out,
+                                      void *const *levels_out, uint32_t *const *signplanes_out, void *hip_stream)
+{
+    const bool levels = levels_out != nullptr;
+    gq_status st = check_params(p, levels, agg_out != nullptr);
+    if (st != GQ_OK) return st;
+    if (!x || K < 1 || K > GQ_MAX_WORKERS || d < 0 || index_base < 0 || (index_base & 3) != 0) return GQ_ERR_INVALID_ARG;
+    if (!agg_out && !dequant_out) return GQ_ERR_INVALID_ARG;
+    if (!aligned(norm, 4)) return GQ_ERR_INVALID_ARG;
+    // the sum is formed in 32-bit registers whatever is stored; a 16-bit store must also hold it
+    const int64_t lim = (agg_out && p->agg == GQ_AGG_I16) ? 32767LL : 2147483647LL;
+    if (max_aggregate(p, K) > lim) return GQ_ERR_OVERFLOW;
+    const bool plane = levels && p->pack >= GQ_PACK_U8_SIGNPLANE;
+    if (plane && !signplanes_out) return GQ_ERR_INVALID_ARG;
+    GradPtrs P;
+    LevelPtrs L;
+    for (int i = 0; i < K; i++) {
+        if (d > 0 && !aligned(x[i], 16)) return GQ_ERR_INVALID_ARG;
+        P.x[i] = x[i];
+        L.lv[i] = nullptr;
+        L.sp[i] = nullptr;
+        if (levels) {
+            if (d > 0 && !aligned(levels_out[i], 16)) return GQ_ERR_INVALID_ARG;
+            L.lv[i] = levels_out[i];
+            if (plane) {
+                if (d > 0 && !aligned(signplanes_out[i], 4)) return GQ_ERR_INVALID_ARG;
+                L.sp[i] = signplanes_out[i];
+            }
+        }
+    }
+    if (d > 0 && ((agg_out && !aligned(agg_out, 16)) || (dequant_out && !aligned(dequant_out, 16)))) return GQ_ERR_INVALID_ARG;
+    if (d == 0) return GQ_OK;
+    if (p->scheme == GQ_LINEAR)
+        return launch_quantize_aggregate<0>(P, L, levels, K, d, norm, p, 0u, index_base, agg_out, dequant_out, (hipStream_t)hip_stream);
+    return launch_quantize_aggregate<1>(P, L, levels, K, d, norm, p, 0u, index_base, agg_out, dequant_out, (hipStream_t)hip_stream);
+}
+
+gq_status gq_int_aggregate(const void *const *levels, const uint32_t *const *signplanes, int K, int64_t d,
+                           const gq_params *p, void *agg_out, void *hip_stream)
+{
+    gq_status st = check_params(p, true, true);
+    if (st != GQ_OK) return st;
+    if (!levels || K < 1 || K > GQ_MAX_WORKERS || d < 0) return GQ_ERR_INVALID_ARG;
+    st = gq_check_width(p, K);
+    if (st != GQ_OK) return st;
+    const bool plane = p->pack >= GQ_PACK_U8_SIGNPLANE;
+    if (plane && !signplanes) return GQ_ERR_INVALID_ARG;
+    LevelCPtrs L;
+    for (int i = 0; i < K; i++) {
+        if (d > 0 && !aligned(levels[i], 16)) return GQ_ERR_INVALID_ARG;
+        L.lv[i] = levels[i];
+        L.sp[i] = nullptr;
+        if (plane) {
+            if (d > 0 && !aligned(signplanes[i], 4)) return GQ_ERR_INVALID_ARG;
+            L.sp[i] = signplanes[i];
+        }
+    }
+    if (d > 0 && !aligned(agg_out, 16)) return GQ_ERR_INVALID_ARG;
+    if (d == 0) return GQ_OK;
+    const bool nibble = (p->pack == GQ_PACK_I4 || p->pack == GQ_PACK_U4_SIGNPLANE);
+    const int64_t per = nibble ? 32 : 16;
+    const int64_t units = (d + per - 1) / per;
+    const int64_t blocks = (units + kBlock - 1) / kBlock;
+    if (!grid_fits(blocks)) return GQ_ERR_INVALID_ARG;
+    const dim3 grid((unsigned)blocks), block(kBlock);
+    hipStream_t s = (hipStream_t)hip_stream;
+#define GQ_AGG(SC, PK) hipLaunchKernelGGL((int_aggregate_kernel<SC, PK>), grid, block, 0, s, L, K, d, agg_out, p->agg)
+    if (p->scheme == GQ_LINEAR) {
+        switch (p->pack) {
+        case GQ_PACK_I8: GQ_AGG(0, GQ_PACK_I8); break;
+        case GQ_PACK_I4: GQ_AGG(0, GQ_PACK_I4); break;
+        case GQ_PACK_U8_SIGNPLANE: GQ_AGG(0, GQ_PACK_U8_SIGNPLANE); break;
+        default: GQ_AGG(0, GQ_PACK_U4_SIGNPLANE); break;
+        }
+    } else {
+        switch (p->pack) {
+        case GQ_PACK_I8: GQ_AGG(1, GQ_PACK_I8); break;
+        case GQ_PACK_I4: GQ_AGG(1, GQ_PACK_I4); break;
+        case GQ_PACK_U8_SIGNPLANE: GQ_AGG(1, GQ_PACK_U8_SIGNPLANE); break;
+        default: GQ_AGG(1, GQ_PACK_U4_SIGNPLANE); break;
+        }
+    }
+#undef GQ_AGG
+    return launched();
+}
+
+gq_status gq_dequantize(const void *agg, int64_t d, const float *norm, const gq_params *p, int K, float *out,
+                        void *hip_stream)
+{
+    const gq_status st = check_params(p, false, true);
+    if (st != GQ_OK) return st;
+    if (K < 1 || K > GQ_MAX_WORKERS || d < 0 || !aligned(norm, 4)) return GQ_ERR_INVALID_ARG;
+    if (d > 0 && (!aligned(agg, 16) || !aligned(out, 16))) return GQ_ERR_INVALID_ARG;
+    if (d == 0) return GQ_OK;
+    const int64_t nvec = (d + 3) / 4;
+    const int64_t blocks = (nvec + kBlock - 1) / kBlock;
+    if (!grid_fits(blocks)) return GQ_ERR_INVALID_ARG;
+    const dim3 grid((unsigned)blocks), block(kBlock);
+    const float div = dequant_divisor(p, K);
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (p->agg == GQ_AGG_I32)
+        hipLaunchKernelGGL(dequantize_kernel<int>, grid, block, 0, s, (const int *)agg, d, norm, div, out);
+    else
+        hipLaunchKernelGGL(dequantize_kernel<short>, grid, block, 0, s, (const short *)agg, d, norm, div, out);
+    return launched();
+}
+
+}  // extern "C"

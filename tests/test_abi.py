@@ -1,0 +1,67 @@
+"""The C-ABI library loads (no GPU needed) and exports every function include/gqsgd.h declares;
+the host-only entry points answer as the header says."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "gqsgd.h")
+
+
+@pytest.fixture(scope="module")
+def gq():
+    from paper_2305_18627_amd import build as B
+    if B.is_stale():
+        B.build()
+    import paper_2305_18627_amd as gq
+    return gq
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", " ", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gq_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(gq):
+    names = declared_functions()
+    assert len(names) >= 9
+    raw = ctypes.CDLL(os.path.join(ROOT, "paper_2305_18627_amd", "libgqsgd.so"))
+    for n in names:
+        assert hasattr(raw, n), n
+    from paper_2305_18627_amd import binding
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_host_only_entry_points(gq):
+    assert gq.version() >= 1000
+    assert gq.status_string(gq.GQ_OK) == "GQ_OK" and gq.status_string(gq.GQ_ERR_OVERFLOW) == "GQ_ERR_OVERFLOW"
+    P = gq.make_params
+    # Section 4.2: n*s (linear) or n*2^(s-1) (exponential) must fit the signed aggregate width
+    assert gq.check_width(P(gq.GQ_LINEAR, 127, agg=gq.GQ_AGG_I32), 16) == gq.GQ_OK
+    assert gq.check_width(P(gq.GQ_LINEAR, 127, agg=gq.GQ_AGG_I16), 64) == gq.GQ_OK          # 8128
+    assert gq.check_width(P(gq.GQ_LINEAR, 1024, agg=gq.GQ_AGG_I16), 32) == gq.GQ_ERR_OVERFLOW  # 32768
+    assert gq.check_width(P(gq.GQ_LINEAR, 1023, agg=gq.GQ_AGG_I16), 32) == gq.GQ_OK         # 32736
+    assert gq.check_width(P(gq.GQ_EXP, 7, agg=gq.GQ_AGG_I16), 32) == gq.GQ_OK               # 2048
+    assert gq.check_width(P(gq.GQ_EXP, 15, agg=gq.GQ_AGG_I16), 32) == gq.GQ_ERR_OVERFLOW    # 2^19
+    assert gq.check_width(P(gq.GQ_EXP, 16, agg=gq.GQ_AGG_I32), 8) == gq.GQ_OK
+    assert gq.check_width(P(gq.GQ_EXP, 31, agg=gq.GQ_AGG_I32), 2) == gq.GQ_ERR_OVERFLOW     # 2^31
+    assert gq.check_width(P(gq.GQ_EXP, 31, agg=gq.GQ_AGG_I32), 1) == gq.GQ_OK               # 2^30
+    assert gq.check_width(P(gq.GQ_LINEAR, 0), 4) == gq.GQ_ERR_INVALID_ARG
+    assert gq.check_width(P(gq.GQ_LINEAR, 5), 0) == gq.GQ_ERR_INVALID_ARG
+    assert gq.check_width(P(gq.GQ_LINEAR, 5), 65) == gq.GQ_ERR_INVALID_ARG
+    assert gq.check_width(P(gq.GQ_EXP, 32), 1) == gq.GQ_ERR_UNSUPPORTED
+    # agreement with the oracle's rule over a grid of settings
+    from oracle import gq_oracle as O
+    for scheme in (0, 1):
+        for s in (1, 2, 3, 7, 15, 16, 31):
+            for K in (1, 2, 4, 16, 32, 64):
+                for agg, bits in ((gq.GQ_AGG_I32, 32), (gq.GQ_AGG_I16, 16)):
+                    ok = gq.check_width(P(scheme, s, agg=agg), K) == gq.GQ_OK
+                    assert ok == O.check_width(scheme, s, K, bits)
+    # workspace: 8 bytes per block partial, at most 1024 blocks per worker, 0 for bad arguments
+    assert gq.norm_workspace_bytes(1, 1) == 8
+    assert gq.norm_workspace_bytes(16, 110_000_000) == 16 * 1024 * 8
+    assert gq.norm_workspace_bytes(65, 10) == 0 and gq.norm_workspace_bytes(1, -1) == 0
