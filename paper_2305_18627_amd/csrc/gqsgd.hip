@@ -137,9 +137,10 @@ __global__ void __launch_bounds__(kBlock) norm_final_kernel(const uint64_t *part
 // =============================================================================================
 // Algorithm 1 lines 2-5 and 9 fused: quantize the K workers' coordinates in registers, add the
 // integer values, write the sum (and/or its dequantised mean, Eq. (1), and/or the packed codes).
-//   SCHEME  0 linear, 1 exponential
-//   KT      compile-time worker count (fully unrolled, K loads in flight), 0 = run-time K
-//   LEVELS  also store every worker's packed codes
+//   SCHEME      0 linear, 1 exponential
+//   KT          compile-time worker count (fully unrolled, K loads in flight), 0 = run-time K
+//   LEVELS      also store every worker's packed codes
+//   UNIFORM_HI  the high word of the Philox call index is the same for the whole launch
 // =============================================================================================
 __device__ __forceinline__ f32x4 load_coords(const float *x, int64_t v, int nvalid)
 {
@@ -195,30 +196,62 @@ __device__ __forceinline__ void store_codes(void *lv, uint32_t *sp, int pack, in
     }
 }
 
-template <int SCHEME, int KT, bool LEVELS>
-__global__ void __launch_bounds__(kBlock)
-quantize_aggregate_kernel(GradPtrs P, LevelPtrs L, int K, int64_t d, const float *__restrict__ norm, int s,
+// Threads per workgroup of the fused kernel.  Small groups retire and refill wave slots at a finer
+// grain, which measurably helps the HBM read/write mix of this kernel (64 > 128 > 256 on MI355X).
+constexpr int kFusedBlock = 128;
+
+// The integer sum of one lane's four coordinates.  Linear codes are summed as floats (exact: the
+// sum stays below 2^24) and converted once; exponential values reach 2^30 and are summed as ints.
+template <int SCHEME> struct Acc;
+template <> struct Acc<0> {
+    float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+    __device__ __forceinline__ void add(float f0, float f1, float f2, float f3) { a0 += f0; a1 += f1; a2 += f2; a3 += f3; }
+    __device__ __forceinline__ i32x4 get() const { return i32x4{(int)a0, (int)a1, (int)a2, (int)a3}; }
+};
+template <> struct Acc<1> {
+    int a0 = 0, a1 = 0, a2 = 0, a3 = 0;
+    __device__ __forceinline__ void add(float f0, float f1, float f2, float f3) { a0 += (int)f0; a1 += (int)f1; a2 += (int)f2; a3 += (int)f3; }
+    __device__ __forceinline__ i32x4 get() const { return i32x4{a0, a1, a2, a3}; }
+};
+
+// The launch covers the 4-coordinate vectors v0 <= v < vend of the buffers.  With UNIFORM_HI the
+// host guarantees that the Philox call index (call_base + v) does not cross a multiple of 2^32 inside
+// the launch, so the high counter word is a scalar: the first round and half of the second are then
+// shared by all lanes or all workers and leave the vector ALU.
+template <int SCHEME, int KT, bool LEVELS, bool UNIFORM_HI>
+__global__ void __launch_bounds__(kFusedBlock)
+quantize_aggregate_kernel(GradPtrs P, LevelPtrs L, int K, int64_t d, int64_t v0, int64_t vend, const float *__restrict__ norm, int s,
                           uint64_t seed, uint32_t worker0, uint64_t call_base, int pack,
                           void *__restrict__ agg_out, int agg_fmt, float *__restrict__ deq_out, float deq_div)
 {
-    const int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t v = v0 + (int64_t)blockIdx.x * kFusedBlock + threadIdx.x;
     const int64_t nfull = d >> 2;
-    const int nvalid = v < nfull ? 4 : (v == nfull ? (int)(d & 3) : 0);
+    const int nvalid = v >= vend ? 0 : (v < nfull ? 4 : (v == nfull ? (int)(d & 3) : 0));
     if (!LEVELS && nvalid == 0) return;          // with LEVELS the sign-plane exchange needs whole waves
 
     const float nrm = *norm;
     const Scale sc = make_scale<SCHEME>(nrm, s);
-    const uint64_t call = call_base + (uint64_t)v;
+    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    uint32_t c_lo, c_hi;
+    if (UNIFORM_HI) {
+        const uint64_t first = call_base + (uint64_t)v0;                      // scalar
+        c_hi = (uint32_t)(first >> 32);
+        c_lo = (uint32_t)first + (uint32_t)(blockIdx.x * kFusedBlock + threadIdx.x);   // no carry (host)
+    } else {
+        const uint64_t call = call_base + (uint64_t)v;
+        c_lo = (uint32_t)call;
+        c_hi = (uint32_t)(call >> 32);
+    }
     const int Kc = KT > 0 ? KT : K;
 
-    int a0 = 0, a1 = 0, a2 = 0, a3 = 0;
+    Acc<SCHEME> acc;
     auto one_worker = [&](int w, const f32x4 &g) {
-        const Words4 r = random_words(seed, worker0 + (uint32_t)w, call);
+        const Words4 r = philox4x32_10(c_lo, c_hi, worker0 + (uint32_t)w, 0u, k0, k1);
         const float f0 = Round<SCHEME>::value(g.x, sc, r.w[0]);
         const float f1 = Round<SCHEME>::value(g.y, sc, r.w[1]);
         const float f2 = Round<SCHEME>::value(g.z, sc, r.w[2]);
         const float f3 = Round<SCHEME>::value(g.w, sc, r.w[3]);
-        a0 += (int)f0; a1 += (int)f1; a2 += (int)f2; a3 += (int)f3;
+        acc.add(f0, f1, f2, f3);
         if (LEVELS) {
             store_codes(L.lv[w], L.sp[w], pack, v, nvalid, d, Round<SCHEME>::code_of_value(f0),
                         Round<SCHEME>::code_of_value(f1), Round<SCHEME>::code_of_value(f2),
@@ -242,39 +275,39 @@ quantize_aggregate_kernel(GradPtrs P, LevelPtrs L, int K, int64_t d, const float
     }
     if (nvalid == 0) return;
 
+    const i32x4 a = acc.get();
     if (agg_out) {
         if (agg_fmt == GQ_AGG_I32) {
             if (nvalid == 4) {
-                const i32x4 o = {a0, a1, a2, a3};
-                __builtin_nontemporal_store(o, reinterpret_cast<i32x4 *>(agg_out) + v);
+                __builtin_nontemporal_store(a, reinterpret_cast<i32x4 *>(agg_out) + v);
             } else {
                 int *o = reinterpret_cast<int *>(agg_out) + (v << 2);
-                o[0] = a0;
-                if (nvalid > 1) o[1] = a1;
-                if (nvalid > 2) o[2] = a2;
+                o[0] = a.x;
+                if (nvalid > 1) o[1] = a.y;
+                if (nvalid > 2) o[2] = a.z;
             }
         } else {
             if (nvalid == 4) {
-                const i16x4 o = {(short)a0, (short)a1, (short)a2, (short)a3};
+                const i16x4 o = {(short)a.x, (short)a.y, (short)a.z, (short)a.w};
                 __builtin_nontemporal_store(o, reinterpret_cast<i16x4 *>(agg_out) + v);
             } else {
                 short *o = reinterpret_cast<short *>(agg_out) + (v << 2);
-                o[0] = (short)a0;
-                if (nvalid > 1) o[1] = (short)a1;
-                if (nvalid > 2) o[2] = (short)a2;
+                o[0] = (short)a.x;
+                if (nvalid > 1) o[1] = (short)a.y;
+                if (nvalid > 2) o[2] = (short)a.z;
             }
         }
     }
     if (deq_out) {
         const float c = sc.scale != 0.0f ? nrm / deq_div : 0.0f;     // Eq. (1): norm / (n * unit)
         if (nvalid == 4) {
-            const f32x4 o = {(float)a0 * c, (float)a1 * c, (float)a2 * c, (float)a3 * c};
+            const f32x4 o = {(float)a.x * c, (float)a.y * c, (float)a.z * c, (float)a.w * c};
             __builtin_nontemporal_store(o, reinterpret_cast<f32x4 *>(deq_out) + v);
         } else {
             float *o = deq_out + (v << 2);
-            o[0] = (float)a0 * c;
-            if (nvalid > 1) o[1] = (float)a1 * c;
-            if (nvalid > 2) o[2] = (float)a2 * c;
+            o[0] = (float)a.x * c;
+            if (nvalid > 1) o[1] = (float)a.y * c;
+            if (nvalid > 2) o[2] = (float)a.z * c;
         }
     }
 }
@@ -437,22 +470,38 @@ static gq_status launch_quantize_aggregate(const GradPtrs &P, const LevelPtrs &L
                                            int64_t index_base, void *agg_out, float *deq_out, hipStream_t st)
 {
     const int64_t nvec = (d + 3) / 4;
-    const int64_t blocks = (nvec + kBlock - 1) / kBlock;
-    if (!grid_fits(blocks)) return GQ_ERR_INVALID_ARG;
-    const dim3 grid((unsigned)blocks), block(kBlock);
     const uint64_t call_base = (uint64_t)index_base / 4u;
     const float div = dequant_divisor(p, K);
-#define GQ_LAUNCH(KT, LV)                                                                                  \
-    hipLaunchKernelGGL((quantize_aggregate_kernel<SCHEME, KT, LV>), grid, block, 0, st, P, L, K, d, norm,  \
-                       p->s, p->seed, worker0, call_base, p->pack, agg_out, p->agg, deq_out, div)
-    if (levels) GQ_LAUNCH(0, true);
-    else if (K == 4) GQ_LAUNCH(4, false);
-    else if (K == 8) GQ_LAUNCH(8, false);
-    else if (K == 16) GQ_LAUNCH(16, false);
-    else if (K == 32) GQ_LAUNCH(32, false);
-    else GQ_LAUNCH(0, false);
+    const dim3 block(kFusedBlock);
+#define GQ_LAUNCH(KT, LV, UH, V0, COUNT)                                                                      \
+    do {                                                                                                      \
+        const int64_t blocks_ = ((COUNT) + kFusedBlock - 1) / kFusedBlock;                                    \
+        if (!grid_fits(blocks_)) return GQ_ERR_INVALID_ARG;                                                   \
+        hipLaunchKernelGGL((quantize_aggregate_kernel<SCHEME, KT, LV, UH>), dim3((unsigned)blocks_), block, 0, st, \
+                           P, L, K, d, (int64_t)(V0), (int64_t)(V0) + (int64_t)(COUNT), norm, p->s, p->seed, worker0, call_base, p->pack,       \
+                           agg_out, p->agg, deq_out, div);                                                    \
+    } while (0)
+    if (levels) {
+        GQ_LAUNCH(0, true, false, 0, nvec);
+        return launched();
+    }
+    // One launch per stretch of vectors whose Philox call index shares its high 32 bits (a second
+    // stretch exists only if the bucket crosses a multiple of 2^34 coordinates).
+    int64_t v0 = 0;
+    while (v0 < nvec) {
+        const uint64_t first = call_base + (uint64_t)v0;
+        const uint64_t room = ((uint64_t)1 << 32) - (first & 0xFFFFFFFFull);
+        const int64_t count = (uint64_t)(nvec - v0) < room ? (nvec - v0) : (int64_t)room;
+        if (K == 4) GQ_LAUNCH(4, false, true, v0, count);
+        else if (K == 8) GQ_LAUNCH(8, false, true, v0, count);
+        else if (K == 16) GQ_LAUNCH(16, false, true, v0, count);
+        else if (K == 32) GQ_LAUNCH(32, false, true, v0, count);
+        else GQ_LAUNCH(0, false, true, v0, count);
+        if (launched() != GQ_OK) return GQ_ERR_DEVICE;
+        v0 += count;
+    }
 #undef GQ_LAUNCH
-    return launched();
+    return GQ_OK;
 }
 
 }  // namespace gq

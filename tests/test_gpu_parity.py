@@ -347,6 +347,29 @@ def test_fused_equals_separate_calls_and_buckets_equal_whole():
         assert torch.equal(agg2, agg)
 
 
+def test_fused_across_the_2_to_34_index_boundary():
+    # the Philox call index g/4 crosses a multiple of 2^32 inside the bucket: the high counter word changes
+    K, d = 16, 70_001
+    xs = gaussians(K, d, seed=99)
+    xh = [host(x) for x in xs]
+    _, nf, _ = oracle_norm(xs, NORMS["linf"])
+    norm_t = dev_scalar(float(nf))
+    for scheme, s in [("linear", 127), ("exp", 16)]:
+        params = gq.make_params(SCHEMES[scheme], s, 0, 0, seed=31337)
+        for base in ((1 << 34) - 4 * 1000, (1 << 34) - 4 * 129, (1 << 34) - 4, 1 << 34, 3 * (1 << 34) - 4 * 17_000):
+            want = O.quantize_aggregate(xh, nf, SCHEMES[scheme], s, params.seed, base)
+            for with_levels in (False, True):
+                agg_out, _, _, _ = run_fused(xs, norm_t, params, base, with_levels)
+                got = host(agg_out)
+                assert np.array_equal(got[:d].astype(np.int64), want) and np.all(got[d:] == 0x5A5A)
+    # and for a run-time worker count
+    params = gq.make_params(0, 127, 0, 0, seed=31337)
+    base = (1 << 34) - 4 * 777
+    want = O.quantize_aggregate(xh[:5], nf, 0, 127, params.seed, base)
+    agg_out, _, _, _ = run_fused(xs[:5], norm_t, params, base, False)
+    assert np.array_equal(host(agg_out)[:d].astype(np.int64), want)
+
+
 def test_unbiased_on_gpu_monte_carlo():
     # E[G(x)] = mean of the workers (Definition 3), measured on the GPU path alone over many seeds
     K, d, T = 4, 2048, 400
