@@ -61,7 +61,10 @@ def test_host_only_entry_points(gq):
                 for agg, bits in ((gq.GQ_AGG_I32, 32), (gq.GQ_AGG_I16, 16)):
                     ok = gq.check_width(P(scheme, s, agg=agg), K) == gq.GQ_OK
                     assert ok == O.check_width(scheme, s, K, bits)
-    # workspace: 8 bytes per block partial, at most 1024 blocks per worker, 0 for bad arguments
+    # workspace: 8 bytes per block partial, bounded (at most 2^16 tile partials or 1024 per worker),
+    # 0 for bad arguments
     assert gq.norm_workspace_bytes(1, 1) == 8
-    assert gq.norm_workspace_bytes(16, 110_000_000) == 16 * 1024 * 8
+    for K, d in ((1, 0), (4, 1 << 20), (16, 110_000_000), (32, 350_000_000), (8, 1_500_000_000), (64, 1 << 40)):
+        b = gq.norm_workspace_bytes(K, d)
+        assert b % 8 == 0 and 8 * K <= b <= 8 * max(1 << 16, 1024 * K)
     assert gq.norm_workspace_bytes(65, 10) == 0 and gq.norm_workspace_bytes(1, -1) == 0
