@@ -34,7 +34,10 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3"])
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--rows", action="store_true",
+                    help="also time every entry point on its own (quantize per worker, int_aggregate, "
+                         "dequantize, fused variants) and report them under \"rows\"")
     ap.add_argument("--cpu-sample", type=int, default=1 << 26, help="coordinates per worker timed on the CPU oracle")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed steps, run three plain 1 GiB device copies (a kernel of known "
@@ -69,6 +72,50 @@ def cpu_baseline(xs, nf, scheme, s, seed, sample, bytes_per_coord):
         "kind": "oracle", "seconds": dt, "coords_per_s": sample / dt,
         "sample": "first %d of %d coordinates of all %d workers (same buffers, same accounting)" % (sample, d, len(xs)),
     }, parts, cuts
+
+
+def time_rows(gq, torch, xs, norm, params, cfg, args):
+    """Every entry point on its own, in the workload's own formats: algorithmic GB/s from HIP events."""
+    K, d = len(xs), xs[0].numel()
+    dev = xs[0].device
+    pack = {"i8": gq.GQ_PACK_I8, "i4": gq.GQ_PACK_I4, "u8s": gq.GQ_PACK_U8_SIGNPLANE, "u4s": gq.GQ_PACK_U4_SIGNPLANE}[cfg["pack"]]
+    aggf = gq.GQ_AGG_I16 if cfg["agg"] == "i16" else gq.GQ_AGG_I32
+    p = gq.make_params(params.scheme, params.s, pack, aggf, seed=params.seed)
+    bits = 4 if pack in (gq.GQ_PACK_I4, gq.GQ_PACK_U4_SIGNPLANE) else 8
+    plane = pack >= gq.GQ_PACK_U8_SIGNPLANE
+    abytes = 2 if aggf == gq.GQ_AGG_I16 else 4
+    lvs = [torch.empty(gq.levels_nbytes(d, pack), dtype=torch.uint8, device=dev) for _ in range(K)]
+    sps = [torch.empty(gq.signplane_nwords(d), dtype=torch.int32, device=dev) for _ in range(K)] if plane else None
+    agg = torch.empty(d, dtype=torch.int16 if abytes == 2 else torch.int32, device=dev)
+    out = torch.empty(d, dtype=torch.float32, device=dev)
+    lvb = bits / 8.0 + (1.0 / 8.0 if plane else 0.0)
+
+    def timed(fn, nbytes):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(max(5, args.steps // 2)):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(); fn(); b.record(); b.synchronize()
+            ts.append(a.elapsed_time(b))
+        ms = sum(ts) / len(ts)
+        return {"ms": ms, "min_ms": min(ts), "GBps": nbytes / ms * 1e-6, "bytes": nbytes}
+
+    def quantize_all():
+        for i in range(K):
+            gq.quantize(xs[i], norm, p, i, 0, lvs[i], sps[i] if plane else None)
+
+    rows = {}
+    rows["quantize_xK"] = timed(quantize_all, K * d * (4.0 + lvb))
+    rows["int_aggregate"] = timed(lambda: gq.int_aggregate(lvs, sps, d, p, agg), d * (K * lvb + abytes))
+    rows["dequantize"] = timed(lambda: gq.dequantize(agg, d, norm, p, K, out), d * (abytes + 4.0))
+    rows["fused_agg"] = timed(lambda: gq.fused_quantize_aggregate(xs, norm, p, 0, agg, None), d * (4.0 * K + abytes))
+    rows["fused_dequant"] = timed(lambda: gq.fused_quantize_aggregate(xs, norm, p, 0, None, out), d * (4.0 * K + 4.0))
+    rows["fused_agg_levels"] = timed(lambda: gq.fused_quantize_aggregate(xs, norm, p, 0, agg, None, lvs, sps),
+                                     d * (4.0 * K + K * lvb + abytes))
+    rows["formats"] = {"pack": cfg["pack"], "agg": cfg["agg"]}
+    return rows
 
 
 def main():
@@ -159,6 +206,8 @@ def main():
                        "dequantize": b_deq / float(np.mean(t_deq)) * 1e-6},
         "norm_flags": int(flags.item()),
     }
+    if args.rows:
+        line["rows"] = time_rows(gq, torch, xs, norm, params, cfg, args)
     if args.calibration_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)

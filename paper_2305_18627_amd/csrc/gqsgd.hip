@@ -392,90 +392,138 @@ quantize_aggregate_kernel(GradPtrs P, LevelPtrs L, int K, int64_t d, int64_t v0,
 }
 
 // =============================================================================================
-// Algorithm 1 line 9 on stored codes: a lane owns 16 bytes of every worker's level buffer
-// (16 coordinates at 8 bits, 32 at 4 bits), widens, adds, and writes int32 or int16 sums.
+// Algorithm 1 lines 2-5 for one worker with the codes stored: a lane owns kQuantVec vectors of four
+// coordinates, kQuantBlock vectors apart, and issues all its loads before the first Philox call.
 // =============================================================================================
+constexpr int kQuantBlock = 128;
+constexpr int kQuantVec = 4;
+
+template <int SCHEME, bool UNIFORM_HI>
+__global__ void __launch_bounds__(kQuantBlock)
+quantize_kernel(const float *__restrict__ x, void *__restrict__ lv, uint32_t *__restrict__ sp, int64_t d,
+                const float *__restrict__ norm, int s, uint64_t seed, uint32_t worker, uint64_t call_base, int pack)
+{
+    const int64_t nfull = d >> 2;
+    const int64_t base = (int64_t)blockIdx.x * (kQuantBlock * kQuantVec) + threadIdx.x;
+    const Scale sc = make_scale<SCHEME>(*norm, s);
+    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    f32x4 g[kQuantVec];
+    int nvalid[kQuantVec];
+#pragma unroll
+    for (int j = 0; j < kQuantVec; j++) {
+        const int64_t v = base + (int64_t)j * kQuantBlock;
+        nvalid[j] = v < nfull ? 4 : (v == nfull ? (int)(d & 3) : 0);
+        g[j] = load_coords(x, v, nvalid[j]);
+    }
+#pragma unroll
+    for (int j = 0; j < kQuantVec; j++) {            // no lane leaves early: the sign-plane exchange needs whole waves
+        const int64_t v = base + (int64_t)j * kQuantBlock;
+        uint32_t c_lo, c_hi;
+        if (UNIFORM_HI) {                             // host: call_base + v stays below the next multiple of 2^32
+            c_hi = (uint32_t)(call_base >> 32);
+            c_lo = (uint32_t)call_base + (uint32_t)v;
+        } else {
+            const uint64_t call = call_base + (uint64_t)v;
+            c_lo = (uint32_t)call;
+            c_hi = (uint32_t)(call >> 32);
+        }
+        const Words4 r = philox4x32_10(c_lo, c_hi, worker, 0u, k0, k1);
+        store_codes(lv, sp, pack, v, nvalid[j], d,
+                    Round<SCHEME>::code_of_value(Round<SCHEME>::value(g[j].x, sc, r.w[0])),
+                    Round<SCHEME>::code_of_value(Round<SCHEME>::value(g[j].y, sc, r.w[1])),
+                    Round<SCHEME>::code_of_value(Round<SCHEME>::value(g[j].z, sc, r.w[2])),
+                    Round<SCHEME>::code_of_value(Round<SCHEME>::value(g[j].w, sc, r.w[3])));
+    }
+}
+
+// =============================================================================================
+// Algorithm 1 line 9 on stored codes.  Same ownership as the fused kernel: a lane owns four
+// coordinates, i.e. one 32-bit (8-bit codes) or 16-bit (4-bit codes) word of every worker's level
+// buffer and a nibble of its sign words; loads and the 128-bit stores of a wave are contiguous.
+// =============================================================================================
+constexpr int kAggBlock = 128;
+
 template <int SCHEME, int PACK>
-__global__ void __launch_bounds__(kBlock)
+__global__ void __launch_bounds__(kAggBlock)
 int_aggregate_kernel(LevelCPtrs L, int K, int64_t d, void *__restrict__ agg_out, int agg_fmt)
 {
     constexpr bool kNibble = (PACK == GQ_PACK_I4 || PACK == GQ_PACK_U4_SIGNPLANE);
     constexpr bool kPlane = (PACK == GQ_PACK_U8_SIGNPLANE || PACK == GQ_PACK_U4_SIGNPLANE);
-    constexpr int kCoords = kNibble ? 32 : 16;
-    const int64_t u = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    const int64_t c0 = u * kCoords;
-    if (c0 >= d) return;
-    const int nvalid = (int)min((int64_t)kCoords, d - c0);
-    const int64_t total_bytes = kNibble ? (d + 1) / 2 : d;
-    const int nbytes = (int)min((int64_t)16, total_bytes - (u << 4));
+    const int64_t v = (int64_t)blockIdx.x * kAggBlock + threadIdx.x;
+    const int64_t nfull = d >> 2;
+    const int nvalid = v < nfull ? 4 : (v == nfull ? (int)(d & 3) : 0);
+    if (nvalid == 0) return;
 
-    int acc[kCoords];
-#pragma unroll
-    for (int i = 0; i < kCoords; i++) acc[i] = 0;
-
-    for (int w = 0; w < K; w++) {
-        u32x4 data;
-        if (nbytes == 16) {
-            data = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(L.lv[w]) + u);
-        } else {
-            const uint8_t *b = reinterpret_cast<const uint8_t *>(L.lv[w]) + (u << 4);
-            uint32_t t[4] = {0u, 0u, 0u, 0u};
-            for (int i = 0; i < nbytes; i++) t[i >> 2] |= (uint32_t)b[i] << (8 * (i & 3));
-            data.x = t[0]; data.y = t[1]; data.z = t[2]; data.w = t[3];
-        }
-        uint32_t signs = 0;
-        if (kPlane) {
-            const uint32_t word = L.sp[w][c0 >> 5];
-            signs = kNibble ? word : ((word >> (16 * (int)(u & 1))) & 0xFFFFu);
-        }
-        const uint32_t dw[4] = {data.x, data.y, data.z, data.w};
-#pragma unroll
-        for (int i = 0; i < kCoords; i++) {
-            const uint32_t word = dw[kNibble ? i >> 3 : i >> 2];
-            int q;
-            if (PACK == GQ_PACK_I8)      q = (int)(int8_t)(word >> (8 * (i & 3)));
-            else if (PACK == GQ_PACK_I4) q = ((int)(word << (28 - 4 * (i & 7)))) >> 28;
-            else if (PACK == GQ_PACK_U8_SIGNPLANE) q = (int)((word >> (8 * (i & 3))) & 255u);
-            else                         q = (int)((word >> (4 * (i & 7))) & 15u);
-            int val;
-            if (SCHEME == 0) {
-                val = q;
-                if (kPlane) val = ((signs >> i) & 1u) ? -q : q;
+    struct Unit { uint32_t codes, signs; };
+    auto fetch = [&](int w) {
+        Unit t;
+        if (!kNibble) {
+            if (nvalid == 4) {
+                t.codes = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(L.lv[w]) + v);
             } else {
-                const bool neg = kPlane ? (((signs >> i) & 1u) != 0u) : (q < 0);
-                const int mag = (int)((1u << abs(q)) >> 1);          // 2^(k-1), 0 for k = 0
-                val = neg ? -mag : mag;
+                const uint8_t *b = reinterpret_cast<const uint8_t *>(L.lv[w]) + (v << 2);
+                t.codes = 0;
+                for (int i = 0; i < nvalid; i++) t.codes |= (uint32_t)b[i] << (8 * i);
             }
-            acc[i] += val;
+        } else {
+            if (nvalid == 4) {
+                t.codes = __builtin_nontemporal_load(reinterpret_cast<const uint16_t *>(L.lv[w]) + v);
+            } else {
+                const uint8_t *b = reinterpret_cast<const uint8_t *>(L.lv[w]) + (v << 1);
+                t.codes = b[0];
+                if (nvalid == 3) t.codes |= (uint32_t)b[1] << 8;
+            }
         }
+        t.signs = kPlane ? (L.sp[w][v >> 3] >> (4 * (int)(v & 7))) & 15u : 0u;
+        return t;
+    };
+    int a0 = 0, a1 = 0, a2 = 0, a3 = 0;
+    auto value = [&](const Unit &t, int i) {
+        int q;
+        if (PACK == GQ_PACK_I8)      q = (int)(int8_t)(t.codes >> (8 * i));
+        else if (PACK == GQ_PACK_I4) q = ((int)(t.codes << (28 - 4 * i))) >> 28;
+        else if (PACK == GQ_PACK_U8_SIGNPLANE) q = (int)((t.codes >> (8 * i)) & 255u);
+        else                         q = (int)((t.codes >> (4 * i)) & 15u);
+        if (SCHEME == 0) return (kPlane && ((t.signs >> i) & 1u)) ? -q : q;
+        const bool neg = kPlane ? (((t.signs >> i) & 1u) != 0u) : (q < 0);
+        const int mag = (int)((1u << abs(q)) >> 1);                  // 2^(k-1), 0 for k = 0
+        return neg ? -mag : mag;
+    };
+    auto add = [&](const Unit &t) { a0 += value(t, 0); a1 += value(t, 1); a2 += value(t, 2); a3 += value(t, 3); };
+    // eight workers' loads are issued before the first is consumed
+    int w = 0;
+    for (; w + 8 <= K; w += 8) {
+        Unit t[8];
+#pragma unroll
+        for (int j = 0; j < 8; j++) t[j] = fetch(w + j);
+#pragma unroll
+        for (int j = 0; j < 8; j++) add(t[j]);
     }
+    for (; w + 2 <= K; w += 2) {
+        const Unit t0 = fetch(w), t1 = fetch(w + 1);
+        add(t0); add(t1);
+    }
+    for (; w < K; w++) add(fetch(w));
 
     if (agg_fmt == GQ_AGG_I32) {
-        int *o = reinterpret_cast<int *>(agg_out) + c0;
-        if (nvalid == kCoords) {
-#pragma unroll
-            for (int i = 0; i < kCoords; i += 4) {
-                const i32x4 t = {acc[i], acc[i + 1], acc[i + 2], acc[i + 3]};
-                __builtin_nontemporal_store(t, reinterpret_cast<i32x4 *>(o + i));
-            }
+        if (nvalid == 4) {
+            const i32x4 o = {a0, a1, a2, a3};
+            __builtin_nontemporal_store(o, reinterpret_cast<i32x4 *>(agg_out) + v);
         } else {
-#pragma unroll
-            for (int i = 0; i < kCoords; i++) if (i < nvalid) o[i] = acc[i];
+            int *o = reinterpret_cast<int *>(agg_out) + (v << 2);
+            o[0] = a0;
+            if (nvalid > 1) o[1] = a1;
+            if (nvalid > 2) o[2] = a2;
         }
     } else {
-        short *o = reinterpret_cast<short *>(agg_out) + c0;
-        if (nvalid == kCoords) {
-#pragma unroll
-            for (int i = 0; i < kCoords; i += 8) {
-                const u32x4 t = {((uint32_t)acc[i] & 0xFFFFu) | ((uint32_t)acc[i + 1] << 16),
-                                 ((uint32_t)acc[i + 2] & 0xFFFFu) | ((uint32_t)acc[i + 3] << 16),
-                                 ((uint32_t)acc[i + 4] & 0xFFFFu) | ((uint32_t)acc[i + 5] << 16),
-                                 ((uint32_t)acc[i + 6] & 0xFFFFu) | ((uint32_t)acc[i + 7] << 16)};
-                __builtin_nontemporal_store(t, reinterpret_cast<u32x4 *>(o + i));
-            }
+        if (nvalid == 4) {
+            const i16x4 o = {(short)a0, (short)a1, (short)a2, (short)a3};
+            __builtin_nontemporal_store(o, reinterpret_cast<i16x4 *>(agg_out) + v);
         } else {
-#pragma unroll
-            for (int i = 0; i < kCoords; i++) if (i < nvalid) o[i] = (short)acc[i];
+            short *o = reinterpret_cast<short *>(agg_out) + (v << 2);
+            o[0] = (short)a0;
+            if (nvalid > 1) o[1] = (short)a1;
+            if (nvalid > 2) o[2] = (short)a2;
         }
     }
 }
@@ -561,7 +609,10 @@ static gq_status launch_quantize_aggregate(const GradPtrs &P, const LevelPtrs &L
                            agg_out, p->agg, deq_out, div);                                                    \
     } while (0)
     if (levels) {
-        GQ_LAUNCH(0, true, false, 0, nvec);
+        // storing codes: one launch; the scalar high word is used when the bucket does not cross 2^34
+        const bool one_stretch = ((call_base & 0xFFFFFFFFull) + (uint64_t)nvec) <= ((uint64_t)1 << 32);
+        if (one_stretch) GQ_LAUNCH(0, true, true, 0, nvec);
+        else GQ_LAUNCH(0, true, false, 0, nvec);
         return launched();
     }
     // One launch per stretch of vectors whose Philox call index shares its high 32 bits (a second
@@ -677,16 +728,22 @@ gq_status gq_quantize(const float *x, int64_t d, const float *norm, const gq_par
     if (d > 0 && (!aligned(x, 16) || !aligned(levels_out, 16))) return GQ_ERR_INVALID_ARG;
     if (d > 0 && plane && !aligned(signplane_out, 4)) return GQ_ERR_INVALID_ARG;
     if (d == 0) return GQ_OK;
-    GradPtrs P;
-    LevelPtrs L;
-    P.x[0] = x;
-    L.lv[0] = levels_out;
-    L.sp[0] = plane ? signplane_out : nullptr;
-    gq_params q = *p;
-    q.agg = GQ_AGG_I32;
-    if (p->scheme == GQ_LINEAR)
-        return launch_quantize_aggregate<0>(P, L, true, 1, d, norm, &q, worker, index_base, nullptr, nullptr, (hipStream_t)hip_stream);
-    return launch_quantize_aggregate<1>(P, L, true, 1, d, norm, &q, worker, index_base, nullptr, nullptr, (hipStream_t)hip_stream);
+    const int64_t nvec = (d + 3) / 4;
+    const int64_t per_block = (int64_t)kQuantBlock * kQuantVec;
+    const int64_t blocks = (nvec + per_block - 1) / per_block;
+    if (!grid_fits(blocks)) return GQ_ERR_INVALID_ARG;
+    const dim3 grid((unsigned)blocks), block(kQuantBlock);
+    const uint64_t call_base = (uint64_t)index_base / 4u;
+    // the high counter word is a scalar unless the bucket (rounded up to whole blocks) crosses 2^34
+    const bool one_stretch = ((call_base & 0xFFFFFFFFull) + (uint64_t)(blocks * per_block)) <= ((uint64_t)1 << 32);
+    uint32_t *sp = plane ? signplane_out : nullptr;
+    hipStream_t st2 = (hipStream_t)hip_stream;
+#define GQ_QUANT(SC, UH) hipLaunchKernelGGL((quantize_kernel<SC, UH>), grid, block, 0, st2, x, levels_out, sp, d, norm, \
+                                            p->s, p->seed, worker, call_base, p->pack)
+    if (p->scheme == GQ_LINEAR) { if (one_stretch) GQ_QUANT(0, true); else GQ_QUANT(0, false); }
+    else                        { if (one_stretch) GQ_QUANT(1, true); else GQ_QUANT(1, false); }
+#undef GQ_QUANT
+    return launched();
 }
 
 gq_status gq_fused_quantize_aggregate(const float *const *x, int K, int64_t d, const float *norm, const gq_params *p,
@@ -749,12 +806,10 @@ gq_status gq_int_aggregate(const void *const *levels, const uint32_t *const *sig
     }
     if (d > 0 && !aligned(agg_out, 16)) return GQ_ERR_INVALID_ARG;
     if (d == 0) return GQ_OK;
-    const bool nibble = (p->pack == GQ_PACK_I4 || p->pack == GQ_PACK_U4_SIGNPLANE);
-    const int64_t per = nibble ? 32 : 16;
-    const int64_t units = (d + per - 1) / per;
-    const int64_t blocks = (units + kBlock - 1) / kBlock;
+    const int64_t nvec = (d + 3) / 4;
+    const int64_t blocks = (nvec + kAggBlock - 1) / kAggBlock;
     if (!grid_fits(blocks)) return GQ_ERR_INVALID_ARG;
-    const dim3 grid((unsigned)blocks), block(kBlock);
+    const dim3 grid((unsigned)blocks), block(kAggBlock);
     hipStream_t s = (hipStream_t)hip_stream;
 #define GQ_AGG(SC, PK) hipLaunchKernelGGL((int_aggregate_kernel<SC, PK>), grid, block, 0, s, L, K, d, agg_out, p->agg)
     if (p->scheme == GQ_LINEAR) {
