@@ -34,7 +34,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--rows", action="store_true",
                     help="also time every entry point on its own (quantize per worker, int_aggregate, "
                          "dequantize, fused variants) and report them under \"rows\"")
@@ -143,16 +143,26 @@ def main():
     norm = torch.zeros(1, device=dev)
     flags = torch.zeros(1, dtype=torch.int32, device=dev)
     ws = torch.empty(gq.norm_workspace_bytes(K, d), dtype=torch.uint8, device=dev)
-    agg = torch.empty(d, dtype=torch.int32, device=dev)
+    agg = torch.empty(0 if cfg.get("bucket") else d, dtype=torch.int32, device=dev)
     out = torch.empty(d, dtype=torch.float32, device=dev)
+
+    bucket = cfg.get("bucket")
+    views = None
+    if bucket:      # bucketed workload: per bucket one fused quantize+aggregate+dequantize call, offsets passed on
+        views = [(lo, [x[lo:min(d, lo + bucket)] for x in xs], out[lo:min(d, lo + bucket)]) for lo in range(0, d, bucket)]
 
     def step(ev=None):
         if ev: ev[0].record()
         gq.global_norm(xs, kind, norm, flags, ws)
         if ev: ev[1].record()
-        gq.fused_quantize_aggregate(xs, norm, params, 0, agg, None)
-        if ev: ev[2].record()
-        gq.dequantize(agg, d, norm, params, K, out)
+        if bucket:
+            for lo, xv, ov in views:
+                gq.fused_quantize_aggregate(xv, norm, params, lo, None, ov)
+            if ev: ev[2].record()
+        else:
+            gq.fused_quantize_aggregate(xs, norm, params, 0, agg, None)
+            if ev: ev[2].record()
+            gq.dequantize(agg, d, norm, params, K, out)
         if ev: ev[3].record()
 
     for _ in range(args.warmup):
@@ -173,7 +183,7 @@ def main():
     # algorithmic bytes: what the method must move (every gradient coordinate read once per pass)
     b_norm = 4.0 * K * d
     b_fused = (4.0 * K + 4.0) * d
-    b_deq = 8.0 * d
+    b_deq = 0.0 if bucket else 8.0 * d
     fused_ms = float(np.mean(t_fused))
     fused_gbps = b_fused / fused_ms * 1e-6
     step_gbps = (b_norm + b_fused + b_deq) / ms_per_step * 1e-6
@@ -186,13 +196,15 @@ def main():
             traffic = None
 
     line = {
-        "metric": "fused quantize+aggregate GB/s and % of HBM peak, d=110M K=16 fp32",
+        "metric": ("fused quantize+aggregate GB/s and % of HBM peak, d=110M K=16 fp32" if args.workload == "c3" else
+                   "fused quantize+aggregate GB/s and %% of HBM peak, workload %s (d=%d K=%d fp32)" % (args.workload, d, K)),
         "value": fused_gbps, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: d=%d fp32 per worker, K=%d resident workers, %s, %s norm, %s dithering s=%d, "
                                "int32 integer sum" % (args.workload, d, K, cfg["dist"], cfg["norm"], cfg["scheme"], s),
-                   "step": "global_norm -> fused quantize+aggregate -> dequantize", "seed": SI.QUANT_SEED},
+                   "step": ("global_norm -> per bucket fused quantize+aggregate+dequantize" if bucket
+                            else "global_norm -> fused quantize+aggregate -> dequantize"), "seed": SI.QUANT_SEED},
         "pct_of_hbm_peak": 100.0 * fused_gbps / HBM_PEAK_GBPS,
         "output_coords_per_s": d / fused_ms * 1e3,
         "roofline": {"bound": "hbm", "achieved": fused_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
@@ -202,8 +214,9 @@ def main():
         "step_GBps": step_gbps, "step_algorithmic_bytes": b_norm + b_fused + b_deq, "wall_ms_per_step": wall_ms / args.steps,
         "calls_ms": {"global_norm": float(np.mean(t_norm)), "fused_quantize_aggregate": fused_ms,
                      "dequantize": float(np.mean(t_deq))},
+        "buckets": len(views) if views else None,
         "calls_GBps": {"global_norm": b_norm / float(np.mean(t_norm)) * 1e-6, "fused_quantize_aggregate": fused_gbps,
-                       "dequantize": b_deq / float(np.mean(t_deq)) * 1e-6},
+                       "dequantize": (b_deq / float(np.mean(t_deq)) * 1e-6) if b_deq else None},
         "norm_flags": int(flags.item()),
     }
     if args.rows:
@@ -219,8 +232,11 @@ def main():
         nf = np.float32(norm.item())
         base, parts, cuts = cpu_baseline(xs, nf, scheme, s, SI.QUANT_SEED, args.cpu_sample, 4.0 * K + 4.0)
         # the sample doubles as a parity check of the timed launch
-        got = agg[:cuts[-1][1]].cpu().numpy().astype(np.int64)
-        base["matches_gpu"] = bool(all(np.array_equal(got[lo:hi], p) for (lo, hi), p in zip(cuts, parts)))
+        if bucket:
+            base["matches_gpu"] = None          # the bucketed step stores the mean only
+        else:
+            got = agg[:cuts[-1][1]].cpu().numpy().astype(np.int64)
+            base["matches_gpu"] = bool(all(np.array_equal(got[lo:hi], p) for (lo, hi), p in zip(cuts, parts)))
         line["cpu_baseline"] = base
     print(json.dumps(line))
 
