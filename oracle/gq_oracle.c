@@ -15,6 +15,8 @@
  *   Algorithm 1 line 9      aggregation = plain sum of the level integers          -> gqo_aggregate
  *   Section 4.2             headroom rule for the sum at a given integer width     -> gqo_check_width, gqo_fits_width
  *   Eq. (1)                 norm * (1/n) * sum                                     -> gqo_dequantize
+ *   Algorithm 2, Sec. 4.3   reduce function on (sign, exponent) pairs, tree order  -> gqo_alg2_k, gqo_exp_reduce_pair,
+ *                                                                                     gqo_exp_tree_reduce, gqo_exp_reduce_dequantize
  *
  * Stored level integer ("code").  The paper numbers levels downwards, l_0 = 1 > ... > l_s = 0.
  * The integer that is stored and summed is k = s - u for level l_u, so k = 0 is the zero level:
@@ -45,6 +47,17 @@
  *                z >= 1: z = 2^e * (1 + m/2^23); round up iff m + R >= 2^23: probability m/2^23 =
  *                (z - 2^e)/2^e exactly as Eq. (2) asks.   z < 1: m = z*2^23 rounded to nearest
  *                integer (ties to even); round up to the smallest level iff m + R >= 2^23.
+ *   - Algorithm 2 (the paper's own aggregation for the exponential grid, kept beside the integer sum):
+ *     values are prescaled by 1/(2 n'), n' = n rounded up to a power of two, so that a code k >= 1 of the
+ *     exponential grid becomes the exponent e = s - k + 1 + log2(n') of sign * 2^-e, and e = 0 is zero
+ *     (Section 4.3).  The listing takes p and m without defining them in the listing; the text has
+ *     p ~ U[0,1] and P(k > b) = 2^-b.  Here k = 1 + (number of leading zero bits of a 32-bit word r), which
+ *     has exactly that law for b <= 32; the paper's cap m = s+1 on k is not applied (it only matters with
+ *     probability 2^-(s+1)).  One word per (tree node, coordinate): Philox counter (lo32(g/4), hi32(g/4),
+ *     node, 1), word g mod 4; nodes are numbered as a binary heap (root 1, children 2h and 2h+1, worker i is
+ *     leaf n' + i, missing workers are zeros); operand 1 of a node is its child 2h.
+ *     In the second-sign case the probability is printed as 2^(e2-e1-1); the text's equivalent form
+ *     "k > e2 - e1 - 1" and unbiasedness both give 2^-(e2-e1-1), which is what the listing computes.
  *   - top of the range: |x| = norm can land one ulp above s after rounding; the code is clamped to s.
  *   - norm == 0, norm not finite, or scale not finite: every code is 0.
  *
@@ -327,4 +340,77 @@ int gqo_quantize_aggregate(const float *const *x, int K, int64_t d, float norm, 
     for (int i = 0; i < K; i++) free(q[i]);
     free(q);
     return rc;
+}
+
+/* ==========================================================================================
+ * Algorithm 2: the reduce function for exponential dithering (Section 4.3).
+ * A pair (sign, e), sign in {-1,+1}, e >= 0, stands for 0 if e = 0 and for sign * 2^-e otherwise.
+ * ========================================================================================== */
+
+/* The random integer k of Algorithm 2 line 1: P(k > b) = 2^-b.  With p = r / 2^32,
+ * k > b  <=>  p < 2^-b  <=>  r has at least b leading zero bits. */
+int gqo_alg2_k(uint32_t r)
+{
+    int lz = 0;
+    for (uint32_t bit = 0x80000000u; bit != 0u && !(r & bit); bit >>= 1) lz++;
+    return lz + 1;
+}
+
+/* Algorithm 2 lines 2-9, in the listing's notation. */
+void gqo_exp_reduce_pair(int sign1, int e1, int sign2, int e2, int k, int *sign_result, int *e_result)
+{
+    int e1_nonzero = e1 > 0;
+    int e2_nonzero = e2 > 0;
+    int sign12 = sign1 * sign2 * e1_nonzero * e2_nonzero;
+    int absdiff = e1 > e2 ? e1 - e2 : e2 - e1;
+    int diff = absdiff - (1 - sign12) / 2;
+    int smaller = ((e1 <= e2) + !e2_nonzero) * e1_nonzero;
+    int nonzero = 1 - (e1 == e2 && sign12 == -1);
+    *sign_result = sign1 * smaller + sign2 * (1 - smaller);
+    *e_result = (e1 * smaller + e2 * (1 - smaller)) * nonzero - sign12 * (k > diff) * nonzero;
+}
+
+static int ceil_log2_int(int n) { int l = 0; while ((1 << l) < n) l++; return l; }
+
+uint32_t gqo_random_word_of(uint64_t seed, uint32_t word2, uint32_t word3, uint64_t g)
+{
+    uint64_t call = g / 4u;
+    uint32_t ctr[4] = { (uint32_t)call, (uint32_t)(call >> 32), word2, word3 };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t out[4];
+    gqo_philox4x32(10, ctr, key, out);
+    return out[g % 4u];
+}
+
+/* Tree reduction of K workers' signed exponential-grid codes with Algorithm 2.
+ * out[j] = sign * e of the root (0 for zero), for the prescale 1/(2 n'), n' = 2^ceil(log2 K). */
+void gqo_exp_tree_reduce(const int32_t *const *q, int K, int64_t d, int s, uint64_t seed, uint64_t index_base,
+                         int32_t *out)
+{
+    int L = ceil_log2_int(K), npad = 1 << L;
+    int sg[2 * 64], ex[2 * 64];
+    for (int64_t j = 0; j < d; j++) {
+        for (int i = 0; i < npad; i++) {
+            int code = i < K ? q[i][j] : 0;
+            int k = code < 0 ? -code : code;
+            sg[npad + i] = code < 0 ? -1 : 1;
+            ex[npad + i] = k ? s - k + 1 + L : 0;           /* 2^(k-s) / (2 n') = 2^-(s-k+1+L) */
+        }
+        for (int h = npad - 1; h >= 1; h--) {
+            uint32_t r = gqo_random_word_of(seed, (uint32_t)h, 1u, index_base + (uint64_t)j);
+            gqo_exp_reduce_pair(sg[2 * h], ex[2 * h], sg[2 * h + 1], ex[2 * h + 1], gqo_alg2_k(r), &sg[h], &ex[h]);
+        }
+        out[j] = ex[1] ? sg[1] * ex[1] : 0;
+    }
+}
+
+/* The mean the reduced pair stands for: sign * 2^-e * (2 n') * norm / K. */
+void gqo_exp_reduce_dequantize(const int32_t *se, int64_t d, double norm, int K, double *out)
+{
+    int L = ceil_log2_int(K);
+    for (int64_t j = 0; j < d; j++) {
+        int e = se[j] < 0 ? -se[j] : se[j];
+        double v = e ? ldexp(1.0, 1 + L - e) : 0.0;
+        out[j] = (se[j] < 0 ? -v : v) * norm / (double)K;
+    }
 }

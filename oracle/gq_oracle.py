@@ -54,6 +54,15 @@ _quantize_aggregate = _sig("gqo_quantize_aggregate", C.c_int, C.POINTER(_f32p), 
                            C.c_float, C.c_int, C.c_int, C.c_uint64, C.c_uint64, _i64p)
 
 
+_alg2_k = _sig("gqo_alg2_k", C.c_int, C.c_uint32)
+_exp_reduce_pair = _sig("gqo_exp_reduce_pair", None, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                        C.POINTER(C.c_int), C.POINTER(C.c_int))
+_random_word_of = _sig("gqo_random_word_of", C.c_uint32, C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint64)
+_exp_tree_reduce = _sig("gqo_exp_tree_reduce", None, C.POINTER(_i32p), C.c_int, C.c_int64, C.c_int, C.c_uint64,
+                        C.c_uint64, _i32p)
+_exp_reduce_dequantize = _sig("gqo_exp_reduce_dequantize", None, _i32p, C.c_int64, C.c_double, C.c_int, _f64p)
+
+
 def _arr(a, dtype):
     a = np.ascontiguousarray(a, dtype=dtype)
     return a
@@ -185,3 +194,36 @@ def quantize_aggregate(xs, norm, scheme, s, seed, index_base=0):
     if rc != 0:
         raise MemoryError("oracle could not allocate the code vectors")
     return A
+
+
+def alg2_k(r):
+    """Algorithm 2 line 1: the random integer k with P(k > b) = 2^-b, from a 32-bit word."""
+    return int(_alg2_k(int(r)))
+
+
+def exp_reduce_pair(sign1, e1, sign2, e2, k):
+    """Algorithm 2 lines 2-9 on (sign, e) pairs standing for sign * 2^-e (e = 0: zero)."""
+    sr, er = C.c_int(0), C.c_int(0)
+    _exp_reduce_pair(int(sign1), int(e1), int(sign2), int(e2), int(k), C.byref(sr), C.byref(er))
+    return sr.value, er.value
+
+
+def random_word_of(seed, word2, word3, g):
+    """Philox4x32-10 word of coordinate g for counter words (lo32(g/4), hi32(g/4), word2, word3)."""
+    return int(_random_word_of(int(seed), int(word2), int(word3), int(g)))
+
+
+def exp_tree_reduce(qs, s, seed, index_base=0):
+    """Algorithm 2 applied in tree order to K workers' exponential-grid codes: sign*e of the root."""
+    rows, ptrs, K, d = _rows(qs, np.int32, C.c_int32)
+    out = np.zeros(d, np.int32)
+    _exp_tree_reduce(ptrs, K, d, int(s), int(seed), int(index_base), _ptr(out, C.c_int32))
+    return out
+
+
+def exp_reduce_dequantize(se, norm, K):
+    """The mean that a reduced (sign, e) stands for: sign * 2^-e * 2n' * norm / K, in binary64."""
+    se = _arr(se, np.int32).reshape(-1)
+    out = np.zeros(se.shape[0], np.float64)
+    _exp_reduce_dequantize(_ptr(se, C.c_int32), se.shape[0], float(norm), int(K), _ptr(out, C.c_double))
+    return out
