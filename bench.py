@@ -114,6 +114,21 @@ def time_rows(gq, torch, xs, norm, params, cfg, args):
     rows["fused_dequant"] = timed(lambda: gq.fused_quantize_aggregate(xs, norm, p, 0, None, out), d * (4.0 * K + 4.0))
     rows["fused_agg_levels"] = timed(lambda: gq.fused_quantize_aggregate(xs, norm, p, 0, agg, None, lvs, sps),
                                      d * (4.0 * K + K * lvb + abytes))
+    if params.scheme == gq.GQ_EXP:
+        # Algorithm 2 on int8 codes: reduced (sign, e) bytes and the fp32 mean; ALU-bound (K-1 Philox calls and
+        # branch-free pair reductions per four coordinates), so GB/s here is far below the HBM roof by design
+        p8 = gq.make_params(params.scheme, params.s, gq.GQ_PACK_I8, gq.GQ_AGG_I32, seed=params.seed)
+        lv8 = lvs if pack == gq.GQ_PACK_I8 else [torch.empty(d, dtype=torch.uint8, device=dev) for _ in range(K)]
+        if lv8 is not lvs:
+            for i in range(K):
+                gq.quantize(xs[i], norm, p8, i, 0, lv8[i])
+        red = torch.empty(d, dtype=torch.int8, device=dev)
+        rows["exp_reduce_alg2"] = timed(lambda: gq.exp_reduce(lv8, d, p8, 0, norm, red, out), d * (K + 1.0 + 4.0))
+        npad = 1
+        while npad < K:
+            npad *= 2
+        rows["exp_reduce_alg2"]["coords_per_s"] = d / rows["exp_reduce_alg2"]["ms"] * 1e3
+        rows["exp_reduce_alg2"]["tree_nodes_per_coordinate"] = npad - 1
     rows["formats"] = {"pack": cfg["pack"], "agg": cfg["agg"]}
     return rows
 

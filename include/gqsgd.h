@@ -155,6 +155,24 @@ gq_status gq_fused_quantize_aggregate(const float *const *x /* host */, int K, i
                                       void *const *levels_out /* host */, uint32_t *const *signplanes_out /* host */,
                                       void *hip_stream);
 
+/* Algorithm 2 (Section 4.3): the paper's own aggregation for the exponential grid, kept beside the
+ * exact integer sum of gq_int_aggregate.  The K workers' codes (written by gq_quantize with GQ_EXP and
+ * GQ_PACK_I8) are moved to the prescaled representation sign * 2^-e, e = s - k + 1 + log2(n'), n' = K
+ * rounded up to a power of two (the paper's division by 2n keeps every partial sum within 1/2), and
+ * reduced pairwise in tree order: nodes numbered as a binary heap (root 1, children 2h and 2h+1, worker i
+ * is leaf n'+i, missing workers are zeros, operand 1 is child 2h); every node rounds its sum to a
+ * neighbouring power of two, upwards iff k > diff as in the listing, with k = 1 + (leading zero bits of
+ * the 32-bit Philox word of counter (lo32(g/4), hi32(g/4), node, 1), word g mod 4), so that P(k > b) = 2^-b.
+ *   levels       host array of K device int8[d] code buffers
+ *   reduced_out  device int8[d]: sign * e of the root (0 for zero), or NULL
+ *   dequant_out  device fp32[d]: the mean it stands for, sign * 2^-e * 2n' * norm / K, or NULL
+ *   norm         device fp32[1]; read only if dequant_out is given
+ * p->pack and p->agg are ignored; p->scheme must be GQ_EXP (else GQ_ERR_UNSUPPORTED).  The result is
+ * unbiased for the exact sum and adds at most a factor 9/8 of second moment per tree level. */
+gq_status gq_exp_reduce(const void *const *levels /* host */, int K, int64_t d, const gq_params *p /* host */,
+                        int64_t index_base, const float *norm, void *reduced_out, float *dequant_out,
+                        void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,7 @@ GQ_AGG_I32, GQ_AGG_I16 = 0, 1
 
 # every symbol include/gqsgd.h declares
 EXPORTS = ("gq_version", "gq_status_string", "gq_check_width", "gq_norm_workspace_bytes", "gq_global_norm",
-           "gq_quantize", "gq_int_aggregate", "gq_dequantize", "gq_fused_quantize_aggregate")
+           "gq_quantize", "gq_int_aggregate", "gq_dequantize", "gq_fused_quantize_aggregate", "gq_exp_reduce")
 
 
 class gq_params(C.Structure):
@@ -52,6 +52,7 @@ def _load():
         "gq_quantize": (i32, [vp, i64, vp, pp, u32, i64, vp, vp, vp]),
         "gq_int_aggregate": (i32, [C.POINTER(vp), C.POINTER(vp), i32, i64, pp, vp, vp]),
         "gq_dequantize": (i32, [vp, i64, vp, pp, i32, vp, vp]),
+        "gq_exp_reduce": (i32, [C.POINTER(vp), i32, i64, pp, i64, vp, vp, vp, vp]),
         "gq_fused_quantize_aggregate": (i32, [C.POINTER(vp), i32, i64, vp, pp, i64, vp, vp, C.POINTER(vp),
                                                C.POINTER(vp), vp]),
     }
@@ -157,3 +158,9 @@ def fused_quantize_aggregate(xs, norm, params, index_base=0, agg_out=None, dequa
                                           _ptr(agg_out), _ptr(dequant_out), _ptr_array(levels_out),
                                           _ptr_array(signplanes_out), _stream(stream))
     _check(st, "gq_fused_quantize_aggregate")
+
+
+def exp_reduce(levels, d, params, index_base=0, norm=None, reduced_out=None, dequant_out=None, stream=None):
+    st = _lib.gq_exp_reduce(_ptr_array(levels), len(levels), int(d), C.byref(params), int(index_base), _ptr(norm),
+                            _ptr(reduced_out), _ptr(dequant_out), _stream(stream))
+    _check(st, "gq_exp_reduce")

@@ -370,6 +370,72 @@ def test_fused_across_the_2_to_34_index_boundary():
     assert np.array_equal(host(agg_out)[:d].astype(np.int64), want)
 
 
+# ------------------------------------------------------------------------------------ Algorithm 2
+@pytest.mark.parametrize("K", [1, 2, 3, 4, 5, 8, 13, 16, 32, 33, 64])
+@pytest.mark.parametrize("s,d", [(7, 70_003), (16, 4099), (31, 1021), (1, 255)])
+def test_exp_reduce_matches_oracle(K, s, d):
+    # the paper's reduce function for exponential dithering, tree order: reduced (sign, e) bit-exact,
+    # the mean it stands for to 1e-5
+    xs = gaussians(K, d, seed=K * 31 + s, std=3e-3)
+    xh = [host(x) for x in xs]
+    _, nf, _ = oracle_norm(xs, NORMS["linf"])
+    norm_t = dev_scalar(float(nf))
+    params = gq.make_params(1, s, 0, 0, seed=SI.QUANT_SEED + s)
+    for base in (0, 4 * 55_555, (1 << 34) - 4 * 100):
+        lvs, qs = [], []
+        for i in range(K):
+            lv, _ = gpu_quantize(xs[i], norm_t, params, i, base)
+            lvs.append(lv)
+            qs.append(O.quantize(xh[i], nf, O.EXP, s, params.seed, i, base))
+            assert np.array_equal(host(lv)[:d].view(np.int8), qs[i].astype(np.int8))
+        red = torch.full((d + 16,), 0x5A, dtype=torch.int8, device=DEV)
+        deq = torch.full((d + 8,), 7.0, device=DEV)
+        gq.exp_reduce(lvs, d, params, base, norm_t, red, deq)
+        torch.cuda.synchronize()
+        want = O.exp_tree_reduce(qs, s, params.seed, base)
+        got = host(red)
+        assert np.array_equal(got[:d].astype(np.int32), want) and np.all(got[d:] == 0x5A)
+        wd = O.exp_reduce_dequantize(want, float(nf), K)
+        gd = host(deq).astype(np.float64)
+        assert np.all(np.abs(gd[:d] - wd) <= RTOL * np.abs(wd))
+        assert np.all(gd[:d][want == 0] == 0.0) and np.all(gd[d:] == 7.0)
+        # outputs are optional one by one
+        red2 = torch.zeros(d, dtype=torch.int8, device=DEV)
+        gq.exp_reduce(lvs, d, params, base, None, red2, None)
+        deq2 = torch.zeros(d, device=DEV)
+        gq.exp_reduce(lvs, d, params, base, norm_t, None, deq2)
+        torch.cuda.synchronize()
+        assert torch.equal(red2, red[:d]) and torch.equal(deq2, deq[:d])
+    with pytest.raises(gq.GQError) as e:
+        gq.exp_reduce(lvs, d, gq.make_params(0, s if s <= 127 else 127), 0, norm_t, red, None)
+    assert e.value.status == gq.GQ_ERR_UNSUPPORTED
+    with pytest.raises(gq.GQError):
+        gq.exp_reduce(lvs, d, params, 0, None, None, None)
+
+
+def test_exp_reduce_is_unbiased_for_the_integer_sum_on_gpu():
+    # E[Algorithm 2 result] = the exact sum that gq_int_aggregate forms, measured over seeds on the GPU
+    K, d, s, T = 16, 4096, 7, 300
+    xs = gaussians(K, d, seed=5, std=3e-3)
+    norm_t = dev_scalar(0.0)
+    gq.global_norm(xs, NORMS["linf"], norm_t)
+    p = gq.make_params(1, s, 0, 0, seed=11)
+    lvs = [gpu_quantize(xs[i], norm_t, p, i, 0)[0] for i in range(K)]
+    agg = torch.zeros(d, dtype=torch.int32, device=DEV)
+    gq.int_aggregate(lvs, None, d, p, agg)
+    exact = torch.zeros(d, device=DEV)
+    gq.dequantize(agg, d, norm_t, p, K, exact)
+    acc = torch.zeros(d, dtype=torch.float64, device=DEV)
+    acc2 = torch.zeros(d, dtype=torch.float64, device=DEV)
+    out = torch.zeros(d, device=DEV)
+    for t in range(T):
+        gq.exp_reduce(lvs, d, gq.make_params(1, s, 0, 0, seed=2000 + t), 0, norm_t, None, out)
+        acc += out.double(); acc2 += out.double() ** 2
+    mean = host(acc) / T
+    sd = np.sqrt(np.maximum(host(acc2) / T - mean * mean, 0.0))
+    assert np.all(np.abs(mean - host(exact).astype(np.float64)) <= 5.0 * sd / np.sqrt(T) + 1e-12)
+
+
 def test_unbiased_on_gpu_monte_carlo():
     # E[G(x)] = mean of the workers (Definition 3), measured on the GPU path alone over many seeds
     K, d, T = 4, 2048, 400
