@@ -106,7 +106,7 @@ norm_tile_kernel(GradPtrs P, int K, int64_t d, int64_t tiles_per_block, uint64_t
             const int64_t v = base + (int64_t)j * kNormTileBlock;
             if (v < nvec) {
                 if (KT > 0) {
-                    f32x4 g[KT > 0 ? KT : 1];
+                    f32x4 g[KT > 0 ? KT : 1];                   // all K loads in flight (measured best, also at K = 32)
 #pragma unroll
                     for (int w = 0; w < KT; w++) g[w] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(P.x[w]) + v);
 #pragma unroll
@@ -338,11 +338,15 @@ quantize_aggregate_kernel(GradPtrs P, LevelPtrs L, int K, int64_t d, int64_t v0,
         }
     };
     if (KT > 0) {
-        f32x4 g[KT > 0 ? KT : 1];
+        constexpr int kInFlight = KT > 16 ? 16 : (KT > 0 ? KT : 1);   // loads issued before the first is consumed
 #pragma unroll
-        for (int w = 0; w < KT; w++) g[w] = load_coords(P.x[w], v, nvalid);
+        for (int w0 = 0; w0 < KT; w0 += kInFlight) {
+            f32x4 g[kInFlight];
 #pragma unroll
-        for (int w = 0; w < KT; w++) one_worker(w, g[w]);
+            for (int j = 0; j < kInFlight; j++) g[j] = load_coords(P.x[w0 + j], v, nvalid);
+#pragma unroll
+            for (int j = 0; j < kInFlight; j++) one_worker(w0 + j, g[j]);
+        }
     } else {
         int w = 0;
         for (; w + 4 <= Kc; w += 4) {
@@ -449,6 +453,25 @@ int_aggregate_kernel(LevelCPtrs L, int K, int64_t d, void *__restrict__ agg_out,
 {
     constexpr bool kNibble = (PACK == GQ_PACK_I4 || PACK == GQ_PACK_U4_SIGNPLANE);
     constexpr bool kPlane = (PACK == GQ_PACK_U8_SIGNPLANE || PACK == GQ_PACK_U4_SIGNPLANE);
+    // Packed two's-complement nibbles are decoded through a 256-entry LDS table indexed by a byte: the
+    // entry holds the integer values of both nibbles, each biased by 128, in its two 16-bit halves, so
+    // that one 32-bit add accumulates two coordinates (K * 192 < 2^16, no carry between the halves).
+    constexpr bool kLut = (PACK == GQ_PACK_I4);
+    constexpr int kBias = 128;
+    __shared__ uint32_t lut[kLut ? 256 : 1];
+    if (kLut) {
+        for (int b = threadIdx.x; b < 256; b += kAggBlock) {
+            uint32_t e = 0;
+            for (int h = 0; h < 2; h++) {
+                const int q = ((int)((uint32_t)b << (28 - 4 * h))) >> 28;
+                const int mag = (int)((1u << abs(q)) >> 1);
+                const int val = SCHEME == 0 ? q : (q < 0 ? -mag : mag);
+                e |= (uint32_t)(val + kBias) << (16 * h);
+            }
+            lut[b] = e;
+        }
+        __syncthreads();
+    }
     const int64_t v = (int64_t)blockIdx.x * kAggBlock + threadIdx.x;
     const int64_t nfull = d >> 2;
     const int nvalid = v < nfull ? 4 : (v == nfull ? (int)(d & 3) : 0);
@@ -489,7 +512,15 @@ int_aggregate_kernel(LevelCPtrs L, int K, int64_t d, void *__restrict__ agg_out,
         const int mag = (int)((1u << abs(q)) >> 1);                  // 2^(k-1), 0 for k = 0
         return neg ? -mag : mag;
     };
-    auto add = [&](const Unit &t) { a0 += value(t, 0); a1 += value(t, 1); a2 += value(t, 2); a3 += value(t, 3); };
+    uint32_t s01 = 0, s23 = 0;
+    auto add = [&](const Unit &t) {
+        if (kLut) {
+            s01 += lut[t.codes & 255u];
+            s23 += lut[(t.codes >> 8) & 255u];
+        } else {
+            a0 += value(t, 0); a1 += value(t, 1); a2 += value(t, 2); a3 += value(t, 3);
+        }
+    };
     // eight workers' loads are issued before the first is consumed
     int w = 0;
     for (; w + 8 <= K; w += 8) {
@@ -504,6 +535,10 @@ int_aggregate_kernel(LevelCPtrs L, int K, int64_t d, void *__restrict__ agg_out,
         add(t0); add(t1);
     }
     for (; w < K; w++) add(fetch(w));
+    if (kLut) {
+        a0 = (int)(s01 & 0xFFFFu) - K * kBias; a1 = (int)(s01 >> 16) - K * kBias;
+        a2 = (int)(s23 & 0xFFFFu) - K * kBias; a3 = (int)(s23 >> 16) - K * kBias;
+    }
 
     if (agg_fmt == GQ_AGG_I32) {
         if (nvalid == 4) {

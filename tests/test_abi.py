@@ -68,3 +68,57 @@ def test_host_only_entry_points(gq):
         b = gq.norm_workspace_bytes(K, d)
         assert b % 8 == 0 and 8 * K <= b <= 8 * max(1 << 16, 1024 * K)
     assert gq.norm_workspace_bytes(65, 10) == 0 and gq.norm_workspace_bytes(1, -1) == 0
+
+
+def test_argument_checks_need_no_device(gq):
+    """Every entry point validates its arguments on the host before anything is enqueued, so the error
+    paths can be exercised without a GPU (the pointers below are never dereferenced)."""
+    import ctypes as C
+    lib = gq.lib()
+    P = gq.make_params
+    fake = C.c_void_p(0x1000)                 # aligned, never touched
+    odd = C.c_void_p(0x1004)                  # 4-byte but not 16-byte aligned
+    arr = (C.c_void_p * 2)(0x1000, 0x2000)
+    bad_arr = (C.c_void_p * 2)(0x1000, 0x2004)
+    ok = P(gq.GQ_LINEAR, 127)
+    I = gq.GQ_ERR_INVALID_ARG
+    # gq_global_norm
+    assert lib.gq_global_norm(arr, 0, 16, 0, fake, None, fake, 1 << 20, None) == I            # K = 0
+    assert lib.gq_global_norm(arr, 2, -1, 0, fake, None, fake, 1 << 20, None) == I            # d < 0
+    assert lib.gq_global_norm(arr, 2, 16, 9, fake, None, fake, 1 << 20, None) == I            # bad kind
+    assert lib.gq_global_norm(bad_arr, 2, 16, 0, fake, None, fake, 1 << 20, None) == I        # misaligned gradient
+    assert lib.gq_global_norm(arr, 2, 16, 0, None, None, fake, 1 << 20, None) == I            # no output
+    assert lib.gq_global_norm(arr, 2, 1 << 20, 0, fake, None, fake, 8, None) == gq.GQ_ERR_WORKSPACE
+    assert lib.gq_global_norm(arr, 2, 1 << 20, 0, fake, None, None, 1 << 20, None) == gq.GQ_ERR_WORKSPACE
+    # gq_quantize
+    q = lambda p, x=fake, d=16, base=0, lv=fake, sp=None: lib.gq_quantize(x, d, fake, C.byref(p), 0, base, lv, sp, None)
+    assert q(ok, x=odd) == I and q(ok, lv=odd) == I and q(ok, base=2) == I and q(ok, base=-4) == I and q(ok, d=-1) == I
+    assert q(P(gq.GQ_LINEAR, 128)) == gq.GQ_ERR_UNSUPPORTED and q(P(gq.GQ_LINEAR, 8, gq.GQ_PACK_I4)) == gq.GQ_ERR_UNSUPPORTED
+    assert q(P(gq.GQ_LINEAR, 256, gq.GQ_PACK_U8_SIGNPLANE), sp=fake) == gq.GQ_ERR_UNSUPPORTED
+    assert q(P(gq.GQ_EXP, 32, gq.GQ_PACK_U8_SIGNPLANE), sp=fake) == gq.GQ_ERR_UNSUPPORTED
+    assert q(P(gq.GQ_LINEAR, 15, gq.GQ_PACK_U4_SIGNPLANE), sp=None) == I                       # sign plane missing
+    assert q(P(2, 15)) == I and q(P(gq.GQ_LINEAR, 0)) == I and q(P(gq.GQ_LINEAR, 5, 9)) == I
+    assert lib.gq_quantize(fake, 16, fake, None, 0, 0, fake, None, None) == I                 # no parameters
+    # gq_fused_quantize_aggregate
+    f = lambda p, K=2, x=arr, agg=fake, deq=None, base=0: lib.gq_fused_quantize_aggregate(
+        x, K, 16, fake, C.byref(p), base, agg, deq, None, None, None)
+    assert f(ok, agg=None) == I and f(ok, K=0) == I and f(ok, K=65) == I and f(ok, x=bad_arr) == I
+    assert f(ok, agg=odd) == I and f(ok, base=6) == I
+    assert f(P(gq.GQ_EXP, 15, agg=gq.GQ_AGG_I16), K=2, x=None) == I
+    big = (C.c_void_p * 32)(*([0x1000] * 32))
+    assert f(P(gq.GQ_EXP, 15, agg=gq.GQ_AGG_I16), K=32, x=big) == gq.GQ_ERR_OVERFLOW
+    assert f(P(gq.GQ_LINEAR, 1024, agg=gq.GQ_AGG_I16), K=32, x=big) == gq.GQ_ERR_OVERFLOW
+    # gq_int_aggregate / gq_dequantize / gq_exp_reduce
+    assert lib.gq_int_aggregate(big, None, 32, 16, C.byref(P(gq.GQ_EXP, 15, gq.GQ_PACK_U4_SIGNPLANE, gq.GQ_AGG_I16)),
+                                fake, None) == gq.GQ_ERR_OVERFLOW
+    assert lib.gq_int_aggregate(arr, None, 2, 16, C.byref(P(gq.GQ_LINEAR, 15, gq.GQ_PACK_U4_SIGNPLANE)), fake, None) == I
+    assert lib.gq_int_aggregate(bad_arr, None, 2, 16, C.byref(ok), fake, None) == I
+    assert lib.gq_int_aggregate(arr, None, 2, 16, C.byref(ok), odd, None) == I
+    assert lib.gq_dequantize(fake, 16, fake, C.byref(ok), 0, fake, None) == I
+    assert lib.gq_dequantize(odd, 16, fake, C.byref(ok), 2, fake, None) == I
+    assert lib.gq_exp_reduce(arr, 2, 16, C.byref(ok), 0, fake, fake, None, None) == gq.GQ_ERR_UNSUPPORTED   # not GQ_EXP
+    ex = P(gq.GQ_EXP, 7)
+    assert lib.gq_exp_reduce(arr, 2, 16, C.byref(ex), 0, fake, None, None, None) == I          # no output
+    assert lib.gq_exp_reduce(arr, 2, 16, C.byref(ex), 2, fake, fake, None, None) == I          # index_base % 4
+    assert lib.gq_exp_reduce(arr, 2, 16, C.byref(ex), 0, None, None, fake, None) == I          # mean without norm
+    assert lib.gq_exp_reduce(bad_arr, 2, 16, C.byref(ex), 0, fake, fake, None, None) == I
