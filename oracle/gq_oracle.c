@@ -17,6 +17,8 @@
  *   Eq. (1)                 norm * (1/n) * sum                                     -> gqo_dequantize
  *   Algorithm 2, Sec. 4.3   reduce function on (sign, exponent) pairs, tree order  -> gqo_alg2_k, gqo_exp_reduce_pair,
  *                                                                                     gqo_exp_tree_reduce, gqo_exp_reduce_dequantize
+ *   Section 7               low-bit linear codes averaged inside every reduce step -> gqo_avg_pair, gqo_avg_tree_reduce,
+ *                                                                                     gqo_avg_reduce_dequantize
  *
  * Stored level integer ("code").  The paper numbers levels downwards, l_0 = 1 > ... > l_s = 0.
  * The integer that is stored and summed is k = s - u for level l_u, so k = 0 is the zero level:
@@ -58,6 +60,12 @@
  *     leaf n' + i, missing workers are zeros); operand 1 of a node is its child 2h.
  *     In the second-sign case the probability is printed as 2^(e2-e1-1); the text's equivalent form
  *     "k > e2 - e1 - 1" and unbiasedness both give 2^-(e2-e1-1), which is what the listing computes.
+ *   - averaging inside each reduce step (Section 7 says only that the average replaces the sum in every
+ *     step and that each step rounds): a node holds round((a + b) / 2) of its two children, an odd sum
+ *     being rounded up or down with probability 1/2 each, which keeps the result unbiased and inside the
+ *     range of the inputs.  Same tree as above (heap numbering, n' leaves, missing workers are zeros); the
+ *     coin of node h at coordinate g is bit h mod 32 of the Philox word with counter
+ *     (lo32(g/4), hi32(g/4), h / 32, 2), word g mod 4.  The root stands for the mean over n' leaves.
  *   - top of the range: |x| = norm can land one ulp above s after rounding; the code is clamped to s.
  *   - norm == 0, norm not finite, or scale not finite: every code is 0.
  *
@@ -413,4 +421,39 @@ void gqo_exp_reduce_dequantize(const int32_t *se, int64_t d, double norm, int K,
         double v = e ? ldexp(1.0, 1 + L - e) : 0.0;
         out[j] = (se[j] < 0 ? -v : v) * norm / (double)K;
     }
+}
+
+/* ==========================================================================================
+ * Section 7: for low-bit linear dithering the paper averages inside every reduce step instead of
+ * summing until the end, so that the codes never leave their b bits.
+ * ========================================================================================== */
+
+/* One step: the average of two codes, an odd sum rounded down (coin = 0) or up (coin = 1). */
+int32_t gqo_avg_pair(int32_t a, int32_t b, int coin)
+{
+    int32_t m = a + b;
+    int32_t half = (m - (((m % 2) + 2) % 2)) / 2;          /* floor(m / 2), exact for negative m too */
+    return (m % 2 != 0 && coin) ? half + 1 : half;
+}
+
+/* Tree reduction of K workers' linear codes with in-step averaging: the root's code. */
+void gqo_avg_tree_reduce(const int32_t *const *q, int K, int64_t d, uint64_t seed, uint64_t index_base, int32_t *out)
+{
+    int L = ceil_log2_int(K), npad = 1 << L;
+    int32_t node[2 * 64];
+    for (int64_t j = 0; j < d; j++) {
+        for (int i = 0; i < npad; i++) node[npad + i] = i < K ? q[i][j] : 0;
+        for (int h = npad - 1; h >= 1; h--) {
+            uint32_t r = gqo_random_word_of(seed, (uint32_t)(h / 32), 2u, index_base + (uint64_t)j);
+            node[h] = gqo_avg_pair(node[2 * h], node[2 * h + 1], (int)((r >> (h % 32)) & 1u));
+        }
+        out[j] = node[1];
+    }
+}
+
+/* The mean over the K workers that the root code stands for: norm * code/s * n'/K. */
+void gqo_avg_reduce_dequantize(const int32_t *code, int64_t d, double norm, int s, int K, double *out)
+{
+    int npad = 1 << ceil_log2_int(K);
+    for (int64_t j = 0; j < d; j++) out[j] = norm * ((double)code[j] / (double)s) * (double)npad / (double)K;
 }

@@ -63,6 +63,11 @@ _exp_tree_reduce = _sig("gqo_exp_tree_reduce", None, C.POINTER(_i32p), C.c_int, 
 _exp_reduce_dequantize = _sig("gqo_exp_reduce_dequantize", None, _i32p, C.c_int64, C.c_double, C.c_int, _f64p)
 
 
+_avg_pair = _sig("gqo_avg_pair", C.c_int32, C.c_int32, C.c_int32, C.c_int)
+_avg_tree_reduce = _sig("gqo_avg_tree_reduce", None, C.POINTER(_i32p), C.c_int, C.c_int64, C.c_uint64, C.c_uint64, _i32p)
+_avg_reduce_dequantize = _sig("gqo_avg_reduce_dequantize", None, _i32p, C.c_int64, C.c_double, C.c_int, C.c_int, _f64p)
+
+
 def _arr(a, dtype):
     a = np.ascontiguousarray(a, dtype=dtype)
     return a
@@ -226,4 +231,25 @@ def exp_reduce_dequantize(se, norm, K):
     se = _arr(se, np.int32).reshape(-1)
     out = np.zeros(se.shape[0], np.float64)
     _exp_reduce_dequantize(_ptr(se, C.c_int32), se.shape[0], float(norm), int(K), _ptr(out, C.c_double))
+    return out
+
+
+def avg_pair(a, b, coin):
+    """Section 7, one reduce step with averaging: round((a+b)/2), an odd sum going up iff coin."""
+    return int(_avg_pair(int(a), int(b), int(coin)))
+
+
+def avg_tree_reduce(qs, seed, index_base=0):
+    """In-step averaging of K workers' linear codes in tree order: the root's code."""
+    rows, ptrs, K, d = _rows(qs, np.int32, C.c_int32)
+    out = np.zeros(d, np.int32)
+    _avg_tree_reduce(ptrs, K, d, int(seed), int(index_base), _ptr(out, C.c_int32))
+    return out
+
+
+def avg_reduce_dequantize(code, norm, s, K):
+    """The mean over K workers that an averaged code stands for, in binary64."""
+    code = _arr(code, np.int32).reshape(-1)
+    out = np.zeros(code.shape[0], np.float64)
+    _avg_reduce_dequantize(_ptr(code, C.c_int32), code.shape[0], float(norm), int(s), int(K), _ptr(out, C.c_double))
     return out
