@@ -173,6 +173,21 @@ gq_status gq_exp_reduce(const void *const *levels /* host */, int K, int64_t d, 
                         int64_t index_base, const float *norm, void *reduced_out, float *dequant_out,
                         void *hip_stream);
 
+/* Section 7, low-bit linear dithering: the average is taken inside every reduce step instead of summing
+ * until the end, so the codes never leave their b bits (a 4-bit sum over 4 workers would leave one value
+ * bit).  Same tree as gq_exp_reduce (n' = K rounded up to a power of two, heap numbering, missing workers
+ * are zeros).  A node holds round((a + b) / 2); an odd sum is rounded up iff its coin is set, the coin of
+ * node h at coordinate g being bit h mod 32 of the Philox word with counter (lo32(g/4), hi32(g/4), h / 32, 2),
+ * word g mod 4: unbiased, and never outside the range of the inputs.
+ *   levels       host array of K device code buffers in p->pack format (GQ_PACK_I8 or GQ_PACK_I4,
+ *                linear grid; other formats: GQ_ERR_UNSUPPORTED)
+ *   reduced_out  device buffer in the same format: the root's code, which stands for the mean over n' leaves, or NULL
+ *   dequant_out  device fp32[d]: the mean over the K workers, norm * code * n' / (K * s), or NULL
+ *   norm         device fp32[1]; read only if dequant_out is given */
+gq_status gq_avg_reduce(const void *const *levels /* host */, int K, int64_t d, const gq_params *p /* host */,
+                        int64_t index_base, const float *norm, void *reduced_out, float *dequant_out,
+                        void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

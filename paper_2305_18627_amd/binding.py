@@ -21,7 +21,7 @@ GQ_AGG_I32, GQ_AGG_I16 = 0, 1
 
 # every symbol include/gqsgd.h declares
 EXPORTS = ("gq_version", "gq_status_string", "gq_check_width", "gq_norm_workspace_bytes", "gq_global_norm",
-           "gq_quantize", "gq_int_aggregate", "gq_dequantize", "gq_fused_quantize_aggregate", "gq_exp_reduce")
+           "gq_quantize", "gq_int_aggregate", "gq_dequantize", "gq_fused_quantize_aggregate", "gq_exp_reduce", "gq_avg_reduce")
 
 
 class gq_params(C.Structure):
@@ -53,6 +53,7 @@ def _load():
         "gq_int_aggregate": (i32, [C.POINTER(vp), C.POINTER(vp), i32, i64, pp, vp, vp]),
         "gq_dequantize": (i32, [vp, i64, vp, pp, i32, vp, vp]),
         "gq_exp_reduce": (i32, [C.POINTER(vp), i32, i64, pp, i64, vp, vp, vp, vp]),
+        "gq_avg_reduce": (i32, [C.POINTER(vp), i32, i64, pp, i64, vp, vp, vp, vp]),
         "gq_fused_quantize_aggregate": (i32, [C.POINTER(vp), i32, i64, vp, pp, i64, vp, vp, C.POINTER(vp),
                                                C.POINTER(vp), vp]),
     }
@@ -164,3 +165,9 @@ def exp_reduce(levels, d, params, index_base=0, norm=None, reduced_out=None, deq
     st = _lib.gq_exp_reduce(_ptr_array(levels), len(levels), int(d), C.byref(params), int(index_base), _ptr(norm),
                             _ptr(reduced_out), _ptr(dequant_out), _stream(stream))
     _check(st, "gq_exp_reduce")
+
+
+def avg_reduce(levels, d, params, index_base=0, norm=None, reduced_out=None, dequant_out=None, stream=None):
+    st = _lib.gq_avg_reduce(_ptr_array(levels), len(levels), int(d), C.byref(params), int(index_base), _ptr(norm),
+                            _ptr(reduced_out), _ptr(dequant_out), _stream(stream))
+    _check(st, "gq_avg_reduce")

@@ -122,3 +122,11 @@ def test_argument_checks_need_no_device(gq):
     assert lib.gq_exp_reduce(arr, 2, 16, C.byref(ex), 2, fake, fake, None, None) == I          # index_base % 4
     assert lib.gq_exp_reduce(arr, 2, 16, C.byref(ex), 0, None, None, fake, None) == I          # mean without norm
     assert lib.gq_exp_reduce(bad_arr, 2, 16, C.byref(ex), 0, fake, fake, None, None) == I
+    av = P(gq.GQ_LINEAR, 7, gq.GQ_PACK_I4)
+    assert lib.gq_avg_reduce(arr, 2, 16, C.byref(ex), 0, fake, fake, None, None) == gq.GQ_ERR_UNSUPPORTED   # not linear
+    assert lib.gq_avg_reduce(arr, 2, 16, C.byref(P(gq.GQ_LINEAR, 15, gq.GQ_PACK_U4_SIGNPLANE)), 0, fake, fake, None, None) \
+        == gq.GQ_ERR_UNSUPPORTED
+    assert lib.gq_avg_reduce(arr, 2, 16, C.byref(av), 0, fake, None, None, None) == I
+    assert lib.gq_avg_reduce(arr, 2, 16, C.byref(av), 0, None, None, fake, None) == I
+    assert lib.gq_avg_reduce(arr, 0, 16, C.byref(av), 0, fake, fake, None, None) == I
+    assert lib.gq_avg_reduce(arr, 2, 16, C.byref(P(gq.GQ_LINEAR, 8, gq.GQ_PACK_I4)), 0, fake, fake, None, None) == gq.GQ_ERR_UNSUPPORTED

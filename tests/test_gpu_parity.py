@@ -436,6 +436,37 @@ def test_exp_reduce_is_unbiased_for_the_integer_sum_on_gpu():
     assert np.all(np.abs(mean - host(exact).astype(np.float64)) <= 5.0 * sd / np.sqrt(T) + 1e-12)
 
 
+# ------------------------------------------------------------------------------------ Section 7 averaging
+@pytest.mark.parametrize("K", [1, 2, 3, 4, 7, 8, 16, 32, 33, 64])
+@pytest.mark.parametrize("s,pack,d", [(7, "i4", 70_003), (7, "i4", 4098), (127, "i8", 4099), (1, "i4", 255), (15, "i8", 1021)])
+def test_avg_reduce_matches_oracle(K, s, pack, d):
+    xs = gaussians(K, d, seed=K * 17 + s, std=3e-3)
+    xh = [host(x) for x in xs]
+    _, nf, _ = oracle_norm(xs, NORMS["linf"])
+    norm_t = dev_scalar(float(nf))
+    params = gq.make_params(0, s, PACKS[pack], 0, seed=SI.QUANT_SEED + 3 * s)
+    for base in (0, 4 * 31_337, (1 << 34) - 4 * 50):
+        lvs = [gpu_quantize(xs[i], norm_t, params, i, base)[0] for i in range(K)]
+        qs = [O.quantize(xh[i], nf, O.LINEAR, s, params.seed, i, base) for i in range(K)]
+        nb = gq.levels_nbytes(d, PACKS[pack])
+        red = torch.full((nb + 16,), 0x5A, dtype=torch.uint8, device=DEV)
+        deq = torch.full((d + 8,), 7.0, device=DEV)
+        gq.avg_reduce(lvs, d, params, base, norm_t, red, deq)
+        torch.cuda.synchronize()
+        want = O.avg_tree_reduce(qs, params.seed, base)
+        wl, _ = O.pack(want, PACKS[pack])
+        got = host(red)
+        assert np.array_equal(got[:nb], wl) and np.all(got[nb:] == 0x5A)
+        wd = O.avg_reduce_dequantize(want, float(nf), s, K)
+        gd = host(deq).astype(np.float64)
+        assert np.all(np.abs(gd[:d] - wd) <= RTOL * np.abs(wd))
+        assert np.all(gd[:d][want == 0] == 0.0) and np.all(gd[d:] == 7.0)
+    for bad in (gq.make_params(1, 7, PACKS["i4"]), gq.make_params(0, 15, PACKS["u4s"])):
+        with pytest.raises(gq.GQError) as e:
+            gq.avg_reduce(lvs, d, bad, 0, norm_t, red, None)
+        assert e.value.status == gq.GQ_ERR_UNSUPPORTED
+
+
 def test_unbiased_on_gpu_monte_carlo():
     # E[G(x)] = mean of the workers (Definition 3), measured on the GPU path alone over many seeds
     K, d, T = 4, 2048, 400
