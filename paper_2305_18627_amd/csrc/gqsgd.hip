@@ -342,8 +342,14 @@ quantize_aggregate_kernel(GradPtrs P, LevelPtrs L, int K, int64_t d, int64_t v0,
 #pragma unroll
         for (int w0 = 0; w0 < KT; w0 += kInFlight) {
             f32x4 g[kInFlight];
+            if (nvalid == 4) {                       // one branch per batch, not per worker
 #pragma unroll
-            for (int j = 0; j < kInFlight; j++) g[j] = load_coords(P.x[w0 + j], v, nvalid);
+                for (int j = 0; j < kInFlight; j++)
+                    g[j] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(P.x[w0 + j]) + v);
+            } else {
+#pragma unroll
+                for (int j = 0; j < kInFlight; j++) g[j] = load_coords(P.x[w0 + j], v, nvalid);
+            }
 #pragma unroll
             for (int j = 0; j < kInFlight; j++) one_worker(w0 + j, g[j]);
         }
