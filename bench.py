@@ -133,6 +133,28 @@ def time_rows(gq, torch, xs, norm, params, cfg, args):
         # Section 7: averaging inside every reduce step; codes in, one code vector and the fp32 mean out
         red = torch.empty(gq.levels_nbytes(d, pack), dtype=torch.uint8, device=dev)
         rows["avg_reduce_sec7"] = timed(lambda: gq.avg_reduce(lvs, d, p, 0, norm, red, out), d * (K * lvb + lvb + 4.0))
+    if pack == gq.GQ_PACK_I8 and d < (1 << 32):
+        # Algorithm 1 lines 6-8: compaction of every worker's non-zero codes, then the sum of the K lists
+        cnts = [torch.zeros(1, dtype=torch.int64, device=dev) for _ in range(K)]
+        ws = torch.empty(max(gq.compact_workspace_bytes(d), 4), dtype=torch.uint8, device=dev)
+        probe_i = torch.empty(1, dtype=torch.int32, device=dev)
+        probe_v = torch.empty(1, dtype=torch.int8, device=dev)
+        for i in range(K):
+            gq.compact(lvs[i], d, p, probe_i, probe_v, cnts[i], ws)
+        torch.cuda.synchronize()
+        nnz = [int(c.item()) for c in cnts]
+        idxs = [torch.empty(max(n, 1), dtype=torch.int32, device=dev) for n in nnz]
+        vals = [torch.empty(max(n, 1), dtype=torch.int8, device=dev) for n in nnz]
+
+        def compact_all():
+            for i in range(K):
+                gq.compact(lvs[i], d, p, idxs[i], vals[i], cnts[i], ws)
+
+        tot = float(sum(nnz))
+        rows["compact_xK"] = timed(compact_all, 2.0 * K * d + 5.0 * tot)
+        if aggf == gq.GQ_AGG_I32:
+            rows["sparse_aggregate"] = timed(lambda: gq.sparse_aggregate(idxs, vals, cnts, d, p, agg), 4.0 * d + 13.0 * tot)
+        rows["nonzero_fraction"] = tot / (float(K) * d)
     rows["formats"] = {"pack": cfg["pack"], "agg": cfg["agg"]}
     return rows
 

@@ -188,6 +188,31 @@ gq_status gq_avg_reduce(const void *const *levels /* host */, int K, int64_t d, 
                         int64_t index_base, const float *norm, void *reduced_out, float *dequant_out,
                         void *hip_stream);
 
+/* Algorithm 1 lines 6-8, the sparse branch: only the non-zero codes are exchanged (Theorem 1 bounds their
+ * number under the (2,2) norm).  Sender side: the (coordinate index, signed code) pairs of the non-zero int8
+ * codes of ONE worker, in increasing index order.
+ *   levels           device int8[d] codes (p->pack must be GQ_PACK_I8; d <= 2^32 - 1, indices are 32-bit)
+ *   indices_out      device uint32[capacity]; values_out device int8[capacity]
+ *   count_out        device uint64[1]: the TRUE number of non-zero codes; if it exceeds `capacity` only the
+ *                    first `capacity` pairs were written and the caller must retry with larger buffers
+ *   workspace        device scratch of at least gq_compact_workspace_bytes(d) bytes (block counts), overwritten
+ * The result is unique (sorted by index) and does not depend on scheduling. */
+size_t gq_compact_workspace_bytes(int64_t d);
+gq_status gq_compact(const void *levels, int64_t d, const gq_params *p /* host */, uint32_t *indices_out,
+                     int8_t *values_out, int64_t capacity, uint64_t *count_out,
+                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Receiver side of the sparse branch: the dense integer sum A_j of the K workers' lists, equal to what
+ * gq_int_aggregate forms from the dense codes.
+ *   indices, values  host arrays of K device lists as written by gq_compact
+ *   counts           host array of K device uint64[1] (read on the device; min(count, capacity) entries are used)
+ *   capacities       host array of K list capacities
+ *   agg_out          device int32[d] (p->agg must be GQ_AGG_I32), fully overwritten
+ * Entries whose index is not below d are ignored.  Returns GQ_ERR_OVERFLOW if gq_check_width(p, K) fails. */
+gq_status gq_sparse_aggregate(const uint32_t *const *indices /* host */, const int8_t *const *values /* host */,
+                              const uint64_t *const *counts /* host */, const int64_t *capacities /* host */,
+                              int K, int64_t d, const gq_params *p /* host */, void *agg_out, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,6 +19,7 @@
  *                                                                                     gqo_exp_tree_reduce, gqo_exp_reduce_dequantize
  *   Section 7               low-bit linear codes averaged inside every reduce step -> gqo_avg_pair, gqo_avg_tree_reduce,
  *                                                                                     gqo_avg_reduce_dequantize
+ *   Algorithm 1 lines 6-8   sparse branch: only the non-zero codes are exchanged   -> gqo_compact, gqo_sparse_aggregate
  *
  * Stored level integer ("code").  The paper numbers levels downwards, l_0 = 1 > ... > l_s = 0.
  * The integer that is stored and summed is k = s - u for level l_u, so k = 0 is the zero level:
@@ -66,6 +67,9 @@
  *     range of the inputs.  Same tree as above (heap numbering, n' leaves, missing workers are zeros); the
  *     coin of node h at coordinate g is bit h mod 32 of the Philox word with counter
  *     (lo32(g/4), hi32(g/4), h / 32, 2), word g mod 4.  The root stands for the mean over n' leaves.
+ *   - sparse branch (Algorithm 1 lines 6-8 say only "Allgather of the non-zero values"): a worker's message
+ *     is the list of (coordinate index, signed code) of its non-zero codes in increasing index order, and the
+ *     receiver adds the integer values of all K lists into a dense sum, which equals the dense aggregate.
  *   - top of the range: |x| = norm can land one ulp above s after rounding; the code is clamped to s.
  *   - norm == 0, norm not finite, or scale not finite: every code is 0.
  *
@@ -456,4 +460,32 @@ void gqo_avg_reduce_dequantize(const int32_t *code, int64_t d, double norm, int 
 {
     int npad = 1 << ceil_log2_int(K);
     for (int64_t j = 0; j < d; j++) out[j] = norm * ((double)code[j] / (double)s) * (double)npad / (double)K;
+}
+
+/* ==========================================================================================
+ * Algorithm 1 lines 6-8: the sparse branch.  What a worker sends is the list of its non-zero
+ * codes with their coordinate indices, in increasing index order; what every receiver forms from
+ * the K lists is the same integer sum as the dense aggregate.
+ * ========================================================================================== */
+
+/* Returns the number of non-zero codes; writes at most `capacity` (index, code) pairs. */
+int64_t gqo_compact(const int32_t *q, int64_t d, int64_t capacity, uint32_t *index_out, int32_t *code_out)
+{
+    int64_t n = 0;
+    for (int64_t j = 0; j < d; j++) {
+        if (q[j] != 0) {
+            if (n < capacity) { index_out[n] = (uint32_t)j; code_out[n] = q[j]; }
+            n++;
+        }
+    }
+    return n;
+}
+
+/* A_j = sum over workers and over their list entries with index j of the integer value of the code. */
+void gqo_sparse_aggregate(const uint32_t *const *index, const int32_t *const *code, const int64_t *count,
+                          int K, int64_t d, int scheme, int64_t *A)
+{
+    for (int64_t j = 0; j < d; j++) A[j] = 0;
+    for (int i = 0; i < K; i++)
+        for (int64_t t = 0; t < count[i]; t++) A[index[i][t]] += gqo_code_value(scheme, code[i][t]);
 }

@@ -68,6 +68,11 @@ _avg_tree_reduce = _sig("gqo_avg_tree_reduce", None, C.POINTER(_i32p), C.c_int, 
 _avg_reduce_dequantize = _sig("gqo_avg_reduce_dequantize", None, _i32p, C.c_int64, C.c_double, C.c_int, C.c_int, _f64p)
 
 
+_compact = _sig("gqo_compact", C.c_int64, _i32p, C.c_int64, C.c_int64, _u32p, _i32p)
+_sparse_aggregate = _sig("gqo_sparse_aggregate", None, C.POINTER(_u32p), C.POINTER(_i32p), _i64p, C.c_int, C.c_int64,
+                         C.c_int, _i64p)
+
+
 def _arr(a, dtype):
     a = np.ascontiguousarray(a, dtype=dtype)
     return a
@@ -253,3 +258,27 @@ def avg_reduce_dequantize(code, norm, s, K):
     out = np.zeros(code.shape[0], np.float64)
     _avg_reduce_dequantize(_ptr(code, C.c_int32), code.shape[0], float(norm), int(s), int(K), _ptr(out, C.c_double))
     return out
+
+
+def compact(q, capacity=None):
+    """Algorithm 1 lines 6-8, sender side: (count, indices, codes) of the non-zero codes, by increasing index.
+    At most `capacity` pairs are returned; count is always the true number."""
+    q = _arr(q, np.int32).reshape(-1)
+    cap = q.shape[0] if capacity is None else int(capacity)
+    idx = np.zeros(max(cap, 1), np.uint32); val = np.zeros(max(cap, 1), np.int32)
+    n = int(_compact(_ptr(q, C.c_int32), q.shape[0], cap, _ptr(idx, C.c_uint32), _ptr(val, C.c_int32)))
+    m = min(n, cap)
+    return n, idx[:m].copy(), val[:m].copy()
+
+
+def sparse_aggregate(indices, codes, d, scheme):
+    """Algorithm 1 lines 6-8, receiver side: the dense integer sum formed from K lists."""
+    K = len(indices)
+    ii = [_arr(a, np.uint32).reshape(-1) for a in indices]
+    cc = [_arr(a, np.int32).reshape(-1) for a in codes]
+    cnt = np.array([a.shape[0] for a in ii], np.int64)
+    ip = (C.POINTER(C.c_uint32) * K)(*[_ptr(a, C.c_uint32) for a in ii])
+    cp = (C.POINTER(C.c_int32) * K)(*[_ptr(a, C.c_int32) for a in cc])
+    A = np.zeros(int(d), np.int64)
+    _sparse_aggregate(ip, cp, _ptr(cnt, C.c_int64), K, int(d), int(scheme), _ptr(A, C.c_int64))
+    return A

@@ -21,7 +21,8 @@ GQ_AGG_I32, GQ_AGG_I16 = 0, 1
 
 # every symbol include/gqsgd.h declares
 EXPORTS = ("gq_version", "gq_status_string", "gq_check_width", "gq_norm_workspace_bytes", "gq_global_norm",
-           "gq_quantize", "gq_int_aggregate", "gq_dequantize", "gq_fused_quantize_aggregate", "gq_exp_reduce", "gq_avg_reduce")
+           "gq_quantize", "gq_int_aggregate", "gq_dequantize", "gq_fused_quantize_aggregate", "gq_exp_reduce", "gq_avg_reduce", "gq_compact_workspace_bytes", "gq_compact",
+           "gq_sparse_aggregate")
 
 
 class gq_params(C.Structure):
@@ -54,6 +55,9 @@ def _load():
         "gq_dequantize": (i32, [vp, i64, vp, pp, i32, vp, vp]),
         "gq_exp_reduce": (i32, [C.POINTER(vp), i32, i64, pp, i64, vp, vp, vp, vp]),
         "gq_avg_reduce": (i32, [C.POINTER(vp), i32, i64, pp, i64, vp, vp, vp, vp]),
+        "gq_compact_workspace_bytes": (sz, [i64]),
+        "gq_compact": (i32, [vp, i64, pp, vp, vp, i64, vp, vp, sz, vp]),
+        "gq_sparse_aggregate": (i32, [C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(i64), i32, i64, pp, vp, vp]),
         "gq_fused_quantize_aggregate": (i32, [C.POINTER(vp), i32, i64, vp, pp, i64, vp, vp, C.POINTER(vp),
                                                C.POINTER(vp), vp]),
     }
@@ -171,3 +175,25 @@ def avg_reduce(levels, d, params, index_base=0, norm=None, reduced_out=None, deq
     st = _lib.gq_avg_reduce(_ptr_array(levels), len(levels), int(d), C.byref(params), int(index_base), _ptr(norm),
                             _ptr(reduced_out), _ptr(dequant_out), _stream(stream))
     _check(st, "gq_avg_reduce")
+
+
+def compact_workspace_bytes(d):
+    return int(_lib.gq_compact_workspace_bytes(int(d)))
+
+
+def compact(levels, d, params, indices_out, values_out, count_out, workspace=None, stream=None):
+    """gq_compact: the non-zero int8 codes of one worker as (index, code) pairs.  Returns the workspace used."""
+    if workspace is None:
+        workspace = torch.empty(max(compact_workspace_bytes(d), 4), dtype=torch.uint8, device=count_out.device)
+    st = _lib.gq_compact(_ptr(levels), int(d), C.byref(params), _ptr(indices_out), _ptr(values_out),
+                         indices_out.numel(), _ptr(count_out), _ptr(workspace),
+                         workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(st, "gq_compact")
+    return workspace
+
+
+def sparse_aggregate(indices, values, counts, d, params, agg_out, stream=None):
+    caps = (C.c_int64 * len(indices))(*[t.numel() for t in indices])
+    st = _lib.gq_sparse_aggregate(_ptr_array(indices), _ptr_array(values), _ptr_array(counts), caps, len(indices),
+                                  int(d), C.byref(params), _ptr(agg_out), _stream(stream))
+    _check(st, "gq_sparse_aggregate")

@@ -467,6 +467,90 @@ def test_avg_reduce_matches_oracle(K, s, pack, d):
         assert e.value.status == gq.GQ_ERR_UNSUPPORTED
 
 
+# ------------------------------------------------------------------------------------ sparse branch
+@pytest.mark.parametrize("d", [1, 15, 16, 17, 4095, 4096, 4097, 70_001, (1 << 20) + 3])
+@pytest.mark.parametrize("density", [0.0, 0.02, 0.5, 1.0])
+def test_compact_matches_oracle(d, density):
+    rng = np.random.default_rng(d % 1000 + int(density * 100))
+    q = rng.integers(-127, 128, d).astype(np.int32)
+    q[q == 0] = 1
+    q[rng.random(d) >= density] = 0
+    lv = torch.from_numpy(q.astype(np.int8)).to(DEV)
+    n, widx, wval = O.compact(q)
+    params = gq.make_params(0, 127, 0, 0, seed=0)
+    cap = d + 5
+    idx = torch.full((cap,), -1, dtype=torch.int32, device=DEV)
+    val = torch.full((cap,), 0x5A, dtype=torch.int8, device=DEV)
+    cnt = torch.full((1,), -1, dtype=torch.int64, device=DEV)
+    gq.compact(lv, d, params, idx, val, cnt)
+    torch.cuda.synchronize()
+    assert int(cnt.item()) == n
+    gi, gv = host(idx).view(np.uint32), host(val)
+    assert np.array_equal(gi[:n], widx) and np.array_equal(gv[:n].astype(np.int32), wval)
+    assert np.all(gi[n:] == 0xFFFFFFFF) and np.all(gv[n:] == 0x5A)          # nothing written past the count
+    if n > 3:                                                                # a short buffer: true count, first entries
+        idx2 = torch.full((3 + 4,), -1, dtype=torch.int32, device=DEV)[:3]
+        val2 = torch.full((3 + 4,), 0x5A, dtype=torch.int8, device=DEV)[:3]
+        gq.compact(lv, d, params, idx2, val2, cnt)
+        torch.cuda.synchronize()
+        assert int(cnt.item()) == n and np.array_equal(host(idx2).view(np.uint32), widx[:3])
+
+
+def test_compact_errors():
+    lv = torch.zeros(64, dtype=torch.int8, device=DEV)
+    idx = torch.zeros(64, dtype=torch.int32, device=DEV)
+    val = torch.zeros(64, dtype=torch.int8, device=DEV)
+    cnt = torch.zeros(1, dtype=torch.int64, device=DEV)
+    with pytest.raises(gq.GQError) as e:
+        gq.compact(lv, 64, gq.make_params(0, 7, PACKS["i4"]), idx, val, cnt)
+    assert e.value.status == gq.GQ_ERR_UNSUPPORTED
+    with pytest.raises(gq.GQError) as e:
+        gq.compact(lv, 1 << 20, gq.make_params(0, 127), idx, val, cnt, workspace=torch.zeros(8, dtype=torch.uint8, device=DEV))
+    assert e.value.status == gq.GQ_ERR_WORKSPACE
+    assert gq.compact_workspace_bytes(-1) == 0 and gq.compact_workspace_bytes(1 << 33) == 0
+    assert gq.compact_workspace_bytes(0) == 4 and gq.compact_workspace_bytes(4097) == 8
+    gq.compact(lv, 0, gq.make_params(0, 127), idx, val, cnt)                # d = 0: count 0
+    torch.cuda.synchronize()
+    assert int(cnt.item()) == 0
+
+
+@pytest.mark.parametrize("scheme,s,kind", [("linear", 15, "l2"), ("linear", 127, "linf"), ("exp", 7, "l2")])
+@pytest.mark.parametrize("K,d", [(1, 1000), (4, 70_001), (16, 300_000)])
+def test_sparse_path_equals_dense_aggregate(scheme, s, kind, K, d):
+    # quantize -> compact each worker -> add the K lists: the same integer sum as the dense path
+    xs = gaussians(K, d, seed=K + d)
+    xh = [host(x) for x in xs]
+    _, nf, _ = oracle_norm(xs, NORMS[kind])
+    norm_t = dev_scalar(float(nf))
+    p = gq.make_params(SCHEMES[scheme], s, 0, 0, seed=4242)
+    lvs = [gpu_quantize(xs[i], norm_t, p, i, 0)[0] for i in range(K)]
+    dense = torch.zeros(d, dtype=torch.int32, device=DEV)
+    gq.int_aggregate(lvs, None, d, p, dense)
+    idxs, vals, cnts = [], [], []
+    total = 0
+    for i in range(K):
+        q = O.quantize(xh[i], nf, SCHEMES[scheme], s, 4242, i, 0)
+        n, widx, wval = O.compact(q)
+        idx = torch.zeros(max(n, 1), dtype=torch.int32, device=DEV)
+        val = torch.zeros(max(n, 1), dtype=torch.int8, device=DEV)
+        cnt = torch.zeros(1, dtype=torch.int64, device=DEV)
+        gq.compact(lvs[i], d, p, idx, val, cnt)
+        torch.cuda.synchronize()
+        assert int(cnt.item()) == n
+        assert np.array_equal(host(idx).view(np.uint32)[:n], widx) and np.array_equal(host(val)[:n].astype(np.int32), wval)
+        idxs.append(idx); vals.append(val); cnts.append(cnt); total += n
+    agg = torch.full((d + 8,), 0x5A5A, dtype=torch.int32, device=DEV)
+    gq.sparse_aggregate(idxs, vals, cnts, d, p, agg)
+    torch.cuda.synchronize()
+    assert torch.equal(agg[:d], dense) and bool((agg[d:] == 0x5A5A).all())
+    want = O.quantize_aggregate(xh, nf, SCHEMES[scheme], s, 4242, 0)
+    assert np.array_equal(host(agg)[:d].astype(np.int64), want)
+    if kind == "l2" and scheme == "linear" and K * d > 10000:
+        # the sparse regime the paper's Theorem 1 speaks of: far fewer non-zeros than coordinates,
+        # within the bound that follows from Eq. (2), s^2 + s*sqrt(nd)
+        assert total <= 1.2 * (s * s + s * np.sqrt(K * d)) and total < 0.2 * K * d
+
+
 def test_unbiased_on_gpu_monte_carlo():
     # E[G(x)] = mean of the workers (Definition 3), measured on the GPU path alone over many seeds
     K, d, T = 4, 2048, 400
