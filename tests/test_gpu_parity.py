@@ -551,6 +551,56 @@ def test_sparse_path_equals_dense_aggregate(scheme, s, kind, K, d):
         assert total <= 1.2 * (s * s + s * np.sqrt(K * d)) and total < 0.2 * K * d
 
 
+def test_step_replays_from_a_hip_graph():
+    # every call only enqueues on the given stream (no allocation, no synchronisation, no memset), so the
+    # whole step can be captured once and replayed; each replay is compared with the eager result on fresh data
+    K, d = 8, 300_001
+    xs = gaussians(K, d, seed=21)
+    p = gq.make_params(0, 127, 0, 0, seed=77)
+    norm_t = dev_scalar(0.0)
+    flags = torch.zeros(1, dtype=torch.int32, device=DEV)
+    ws = torch.empty(gq.norm_workspace_bytes(K, d), dtype=torch.uint8, device=DEV)
+    agg = torch.zeros(d, dtype=torch.int32, device=DEV)
+    out = torch.zeros(d, device=DEV)
+    cidx = torch.zeros(d, dtype=torch.int32, device=DEV)
+    cval = torch.zeros(d, dtype=torch.int8, device=DEV)
+    ccnt = torch.zeros(1, dtype=torch.int64, device=DEV)
+    cws = torch.empty(gq.compact_workspace_bytes(d), dtype=torch.uint8, device=DEV)
+    lv0 = torch.zeros(d, dtype=torch.uint8, device=DEV)
+
+    def step():
+        gq.global_norm(xs, NORMS["l2"], norm_t, flags, ws)
+        gq.fused_quantize_aggregate(xs, norm_t, p, 0, agg, None)
+        gq.dequantize(agg, d, norm_t, p, K, out)
+        gq.quantize(xs[0], norm_t, p, 0, 0, lv0)
+        gq.compact(lv0, d, p, cidx, cval, ccnt, cws)
+
+    step()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    gen = torch.Generator(device="cpu").manual_seed(5)
+    for rep in range(4):
+        for x in xs:                                     # new gradients in the captured buffers
+            x.copy_((torch.randn(d, generator=gen) * (1e-3 * (rep + 1))).to(DEV))
+        agg.fill_(-1); out.fill_(-1.0); norm_t.fill_(-1.0); ccnt.fill_(-1)
+        g.replay()
+        torch.cuda.synchronize()
+        got = (norm_t.clone(), agg.clone(), out.clone(), ccnt.clone(), cidx.clone())
+        agg.fill_(-2); out.fill_(-2.0); norm_t.fill_(-2.0); ccnt.fill_(-2)
+        step()
+        torch.cuda.synchronize()
+        assert torch.equal(got[0], norm_t) and torch.equal(got[1], agg) and torch.equal(got[2], out)
+        assert torch.equal(got[3], ccnt) and torch.equal(got[4][:int(ccnt.item())], cidx[:int(ccnt.item())])
+        assert float(norm_t.item()) > 0 and int(agg.abs().max()) > 0
+
+
 def test_unbiased_on_gpu_monte_carlo():
     # E[G(x)] = mean of the workers (Definition 3), measured on the GPU path alone over many seeds
     K, d, T = 4, 2048, 400
