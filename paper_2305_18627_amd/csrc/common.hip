@@ -1,0 +1,43 @@
+// Entry points that touch no device: version, status names, the integer headroom rule of Section 4.2.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "gqsgd.h"
+#include "gq_device.hpp"
+#include "gq_host.hpp"
+
+namespace gq {
+
+
+}  // namespace gq
+
+using namespace gq;
+
+extern "C" {
+
+int gq_version(void) { return 1000; }
+
+const char *gq_status_string(gq_status st)
+{
+    switch (st) {
+    case GQ_OK: return "GQ_OK";
+    case GQ_ERR_INVALID_ARG: return "GQ_ERR_INVALID_ARG";
+    case GQ_ERR_UNSUPPORTED: return "GQ_ERR_UNSUPPORTED";
+    case GQ_ERR_OVERFLOW: return "GQ_ERR_OVERFLOW";
+    case GQ_ERR_WORKSPACE: return "GQ_ERR_WORKSPACE";
+    case GQ_ERR_DEVICE: return "GQ_ERR_DEVICE";
+    }
+    return "GQ_ERR_UNKNOWN";
+}
+
+gq_status gq_check_width(const gq_params *p, int K)
+{
+    const gq_status st = check_params(p, false, true);
+    if (st != GQ_OK) return st;
+    if (K < 1 || K > GQ_MAX_WORKERS) return GQ_ERR_INVALID_ARG;
+    const int64_t lim = p->agg == GQ_AGG_I32 ? 2147483647LL : 32767LL;
+    return max_aggregate(p, K) <= lim ? GQ_OK : GQ_ERR_OVERFLOW;
+}
+
+}  // extern "C"

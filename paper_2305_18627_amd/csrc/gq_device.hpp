@@ -14,6 +14,11 @@ typedef short i16x4 __attribute__((ext_vector_type(4)));
 constexpr int kBlock = 256;          // threads per workgroup: four wave64
 constexpr int kMaxWorkers = 64;
 
+// Per-worker device pointers, passed to the kernels by value.
+struct GradPtrs { const float *x[kMaxWorkers]; };
+struct LevelPtrs { void *lv[kMaxWorkers]; uint32_t *sp[kMaxWorkers]; };
+struct LevelCPtrs { const void *lv[kMaxWorkers]; const uint32_t *sp[kMaxWorkers]; };
+
 // ---------------------------------------------------------------------------------------------
 // Philox4x32-10 (Salmon et al., SC'11).  The 32x32->64 products map to v_mad_u64_u32, the two
 // three-way xors of a round to v_bitop3_b32; the key schedule depends on the seed only and stays in

@@ -1,0 +1,48 @@
+// Host-side helpers shared by the entry points: argument checks and launch bookkeeping.
+// Internal to the library; the public surface is include/gqsgd.h.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "gqsgd.h"
+
+namespace gq {
+
+static inline bool aligned(const void *p, size_t a) { return p != nullptr && ((uintptr_t)p % a) == 0; }
+
+static inline gq_status check_params(const gq_params *p, bool uses_pack, bool uses_agg)
+{
+    if (!p) return GQ_ERR_INVALID_ARG;
+    if (p->scheme != GQ_LINEAR && p->scheme != GQ_EXP) return GQ_ERR_INVALID_ARG;
+    if (p->s < 1) return GQ_ERR_INVALID_ARG;
+    if (p->scheme == GQ_LINEAR && p->s > 32767) return GQ_ERR_UNSUPPORTED;
+    if (p->scheme == GQ_EXP && p->s > 31) return GQ_ERR_UNSUPPORTED;
+    if (uses_pack) {
+        if (p->pack < GQ_PACK_I8 || p->pack > GQ_PACK_U4_SIGNPLANE) return GQ_ERR_INVALID_ARG;
+        const int lim = p->pack == GQ_PACK_I8 ? 127 : p->pack == GQ_PACK_I4 ? 7 : p->pack == GQ_PACK_U8_SIGNPLANE ? 255 : 15;
+        if (p->s > lim) return GQ_ERR_UNSUPPORTED;
+    }
+    if (uses_agg && p->agg != GQ_AGG_I32 && p->agg != GQ_AGG_I16) return GQ_ERR_INVALID_ARG;
+    return GQ_OK;
+}
+
+static inline int64_t max_aggregate(const gq_params *p, int K)
+{
+    return p->scheme == GQ_LINEAR ? (int64_t)K * p->s : (int64_t)K * ((int64_t)1 << (p->s - 1));
+}
+
+static inline float dequant_divisor(const gq_params *p, int K)
+{
+    // n * (1/unit): K*s or K*2^(s-1); both are exact in binary32 for the supported ranges
+    return p->scheme == GQ_LINEAR ? (float)((int64_t)K * p->s) : (float)K * (float)((int64_t)1 << (p->s - 1));
+}
+
+static inline gq_status launched()
+{
+    return hipGetLastError() == hipSuccess ? GQ_OK : GQ_ERR_DEVICE;
+}
+
+static inline bool grid_fits(int64_t blocks) { return blocks >= 0 && blocks <= 0x7FFFFFFF; }
+
+}  // namespace gq

@@ -1,0 +1,342 @@
+// Tree reductions of stored codes on MI355X (gfx950): Algorithm 2 for the exponential grid and the
+// in-step averaging of Section 7 for low-bit linear codes.  Contracts: include/gqsgd.h.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "gqsgd.h"
+#include "gq_device.hpp"
+#include "gq_host.hpp"
+
+namespace gq {
+
+// =============================================================================================
+// Algorithm 2 (Section 4.3): the paper's own aggregation for the exponential grid.  Codes are moved
+// to the prescaled representation sign * 2^-e, e = s - k + 1 + log2(n'), and reduced pairwise in
+// tree order; every node rounds its sum to a neighbouring power of two with the random integer
+// k, P(k > b) = 2^-b.  A lane owns four coordinates and walks the tree depth first with a stack of
+// log2(n') + 1 partial results, so the K code words are consumed as they arrive.
+// One signed int holds a pair: se = sign * e (0 for zero).
+// =============================================================================================
+constexpr int kReduceBlock = 128;
+
+__device__ __forceinline__ int alg2_pair(int se1, int se2, uint32_t r)
+{
+    const int k = __clz((int)r) + 1;                       // P(k > b) = 2^-b; 33 for r = 0
+    const int e1 = abs(se1), e2 = abs(se2);
+    const bool both = (e1 > 0) && (e2 > 0);
+    const bool opposite = both && ((se1 ^ se2) < 0);        // sign12 = -1
+    const bool same = both && ((se1 ^ se2) >= 0);           // sign12 = +1
+    const int diff = abs(e1 - e2) - (opposite ? 1 : 0);
+    const bool smaller = (e1 > 0) && (e1 <= e2 || e2 == 0); // operand 1 has the larger magnitude
+    const bool nonzero = !(opposite && e1 == e2);
+    const int sel = smaller ? se1 : se2;
+    const int e_sel = smaller ? e1 : e2;
+    const int adj = (k > diff) ? (same ? -1 : (opposite ? 1 : 0)) : 0;
+    const int e = nonzero ? e_sel + adj : 0;
+    return sel < 0 ? -e : e;
+}
+
+template <int NPAD, bool UNIFORM_HI>
+__global__ void __launch_bounds__(kReduceBlock)
+exp_reduce_kernel(LevelCPtrs Lv, int K, int64_t d, int s, uint64_t seed, uint64_t call_base,
+                  const float *__restrict__ norm, void *__restrict__ reduced_out, float *__restrict__ deq_out)
+{
+    constexpr int L = NPAD == 1 ? 0 : NPAD == 2 ? 1 : NPAD == 4 ? 2 : NPAD == 8 ? 3 : NPAD == 16 ? 4 : NPAD == 32 ? 5 : 6;
+    const int64_t v = (int64_t)blockIdx.x * kReduceBlock + threadIdx.x;
+    const int64_t nfull = d >> 2;
+    const int nvalid = v < nfull ? 4 : (v == nfull ? (int)(d & 3) : 0);
+    if (nvalid == 0) return;
+    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    uint32_t c_lo, c_hi;
+    if (UNIFORM_HI) {
+        c_hi = (uint32_t)(call_base >> 32);
+        c_lo = (uint32_t)call_base + (uint32_t)v;           // no carry (host)
+    } else {
+        const uint64_t call = call_base + (uint64_t)v;
+        c_lo = (uint32_t)call;
+        c_hi = (uint32_t)(call >> 32);
+    }
+    auto fetch = [&](int w) -> uint32_t {
+        if (w >= K) return 0u;                              // missing workers are zero leaves
+        if (nvalid == 4) return __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(Lv.lv[w]) + v);
+        const uint8_t *b = reinterpret_cast<const uint8_t *>(Lv.lv[w]) + (v << 2);
+        uint32_t t = 0;
+        for (int i = 0; i < nvalid; i++) t |= (uint32_t)b[i] << (8 * i);
+        return t;
+    };
+    // code k >= 1 of the exponential grid -> e = s - k + 1 + L; 0 stays 0
+    auto leaf = [&](uint32_t word, int i) -> int {
+        const int q = (int)(int8_t)(word >> (8 * i));
+        const int e = q ? s + 1 + L - abs(q) : 0;
+        return q < 0 ? -e : e;
+    };
+    int st[L + 1][4];                                       // the stack of partial results
+    constexpr int kBatch = NPAD < 8 ? NPAD : 8;
+#pragma unroll
+    for (int w0 = 0; w0 < NPAD; w0 += kBatch) {
+        uint32_t words[kBatch];
+#pragma unroll
+        for (int j = 0; j < kBatch; j++) words[j] = fetch(w0 + j);
+#pragma unroll
+        for (int j = 0; j < kBatch; j++) {
+            const int i = w0 + j;                            // leaf index; the stack depth is popcount(i)
+            int top = __builtin_popcount((unsigned)i);
+#pragma unroll
+            for (int c = 0; c < 4; c++) st[top][c] = leaf(words[j], c);
+#pragma unroll
+            for (int lvl = 1; lvl <= L; lvl++) {
+                if (((i + 1) & ((1 << lvl) - 1)) == 0) {     // a subtree of 2^lvl leaves is complete
+                    const uint32_t node = (uint32_t)((NPAD >> lvl) + (i >> lvl));   // heap numbering
+                    const Words4 r = philox4x32_10(c_lo, c_hi, node, 1u, k0, k1);
+#pragma unroll
+                    for (int c = 0; c < 4; c++) st[top - 1][c] = alg2_pair(st[top - 1][c], st[top][c], r.w[c]);
+                    top--;
+                }
+            }
+        }
+    }
+    if (reduced_out) {
+        const uint32_t wout = (uint32_t)(st[0][0] & 255) | ((uint32_t)(st[0][1] & 255) << 8) |
+                              ((uint32_t)(st[0][2] & 255) << 16) | ((uint32_t)(st[0][3] & 255) << 24);
+        if (nvalid == 4) {
+            __builtin_nontemporal_store(wout, reinterpret_cast<uint32_t *>(reduced_out) + v);
+        } else {
+            uint8_t *b = reinterpret_cast<uint8_t *>(reduced_out) + (v << 2);
+            for (int i = 0; i < nvalid; i++) b[i] = (uint8_t)(wout >> (8 * i));
+        }
+    }
+    if (deq_out) {
+        // the mean the pair stands for: sign * 2^-e * (2 n') * norm / K
+        const float nrm = *norm;
+        const float c = (nrm > 0.0f && nrm <= 3.402823466e+38f) ? nrm / (float)K : 0.0f;
+        float o[4];
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const int se = st[0][i], e = abs(se);
+            const float p2 = __uint_as_float((uint32_t)(127 + 1 + L - e) << 23);     // 2^(1+L-e), e <= s+L <= 37
+            o[i] = e ? (se < 0 ? -(c * p2) : c * p2) : 0.0f;
+        }
+        if (nvalid == 4) {
+            const f32x4 t = {o[0], o[1], o[2], o[3]};
+            __builtin_nontemporal_store(t, reinterpret_cast<f32x4 *>(deq_out) + v);
+        } else {
+            for (int i = 0; i < nvalid; i++) deq_out[(v << 2) + i] = o[i];
+        }
+    }
+}
+
+// =============================================================================================
+// Section 7: low-bit linear codes averaged inside every reduce step, so that they never leave their
+// b bits.  Same tree walk as exp_reduce_kernel; a node holds round((a + b) / 2), an odd sum going
+// up iff its coin is set.  The coins of up to 32 nodes are the bits of ONE Philox word per
+// coordinate (stream 2, counter word 2 = node / 32), so the kernel stays memory-bound.
+// =============================================================================================
+template <int NPAD, bool NIBBLE, bool UNIFORM_HI>
+__global__ void __launch_bounds__(kReduceBlock)
+avg_reduce_kernel(LevelCPtrs Lv, int K, int64_t d, uint64_t seed, uint64_t call_base,
+                  const float *__restrict__ norm, float deq_div, void *__restrict__ reduced_out,
+                  float *__restrict__ deq_out)
+{
+    constexpr int L = NPAD == 1 ? 0 : NPAD == 2 ? 1 : NPAD == 4 ? 2 : NPAD == 8 ? 3 : NPAD == 16 ? 4 : NPAD == 32 ? 5 : 6;
+    const int64_t v = (int64_t)blockIdx.x * kReduceBlock + threadIdx.x;
+    const int64_t nfull = d >> 2;
+    const int nvalid = v < nfull ? 4 : (v == nfull ? (int)(d & 3) : 0);
+    if (nvalid == 0) return;
+    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    uint32_t c_lo, c_hi;
+    if (UNIFORM_HI) {
+        c_hi = (uint32_t)(call_base >> 32);
+        c_lo = (uint32_t)call_base + (uint32_t)v;           // no carry (host)
+    } else {
+        const uint64_t call = call_base + (uint64_t)v;
+        c_lo = (uint32_t)call;
+        c_hi = (uint32_t)(call >> 32);
+    }
+    const Words4 coins0 = philox4x32_10(c_lo, c_hi, 0u, 2u, k0, k1);      // nodes 1..31
+    Words4 coins1 = coins0;
+    if (NPAD == 64) coins1 = philox4x32_10(c_lo, c_hi, 1u, 2u, k0, k1);   // nodes 32..63
+    auto fetch = [&](int w) -> uint32_t {
+        if (w >= K) return 0u;                              // missing workers are zero leaves
+        if (!NIBBLE) {
+            if (nvalid == 4) return __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(Lv.lv[w]) + v);
+            const uint8_t *b = reinterpret_cast<const uint8_t *>(Lv.lv[w]) + (v << 2);
+            uint32_t t = 0;
+            for (int i = 0; i < nvalid; i++) t |= (uint32_t)b[i] << (8 * i);
+            return t;
+        }
+        if (nvalid == 4) return __builtin_nontemporal_load(reinterpret_cast<const uint16_t *>(Lv.lv[w]) + v);
+        const uint8_t *b = reinterpret_cast<const uint8_t *>(Lv.lv[w]) + (v << 1);
+        uint32_t t = b[0];
+        if (nvalid == 3) t |= (uint32_t)b[1] << 8;
+        return t;
+    };
+    auto leaf = [&](uint32_t word, int i) -> int {
+        return NIBBLE ? ((int)(word << (28 - 4 * i))) >> 28 : (int)(int8_t)(word >> (8 * i));
+    };
+    int st[L + 1][4];
+    constexpr int kBatch = NPAD < 8 ? NPAD : 8;
+#pragma unroll
+    for (int w0 = 0; w0 < NPAD; w0 += kBatch) {
+        uint32_t words[kBatch];
+#pragma unroll
+        for (int j = 0; j < kBatch; j++) words[j] = fetch(w0 + j);
+#pragma unroll
+        for (int j = 0; j < kBatch; j++) {
+            const int i = w0 + j;
+            int top = __builtin_popcount((unsigned)i);
+#pragma unroll
+            for (int c = 0; c < 4; c++) st[top][c] = leaf(words[j], c);
+#pragma unroll
+            for (int lvl = 1; lvl <= L; lvl++) {
+                if (((i + 1) & ((1 << lvl) - 1)) == 0) {
+                    const int node = (NPAD >> lvl) + (i >> lvl);
+#pragma unroll
+                    for (int c = 0; c < 4; c++) {
+                        const uint32_t word = node < 32 ? coins0.w[c] : coins1.w[c];
+                        const int coin = (int)((word >> (node & 31)) & 1u);
+                        st[top - 1][c] = (st[top - 1][c] + st[top][c] + coin) >> 1;   // floor or ceil of the average
+                    }
+                    top--;
+                }
+            }
+        }
+    }
+    if (reduced_out) {
+        if (!NIBBLE) {
+            const uint32_t wout = (uint32_t)(st[0][0] & 255) | ((uint32_t)(st[0][1] & 255) << 8) |
+                                  ((uint32_t)(st[0][2] & 255) << 16) | ((uint32_t)(st[0][3] & 255) << 24);
+            if (nvalid == 4) {
+                __builtin_nontemporal_store(wout, reinterpret_cast<uint32_t *>(reduced_out) + v);
+            } else {
+                uint8_t *b = reinterpret_cast<uint8_t *>(reduced_out) + (v << 2);
+                for (int i = 0; i < nvalid; i++) b[i] = (uint8_t)(wout >> (8 * i));
+            }
+        } else {
+            uint32_t wout = (uint32_t)(st[0][0] & 15);
+            if (nvalid > 1) wout |= (uint32_t)(st[0][1] & 15) << 4;
+            if (nvalid > 2) wout |= (uint32_t)(st[0][2] & 15) << 8;
+            if (nvalid > 3) wout |= (uint32_t)(st[0][3] & 15) << 12;
+            if (nvalid == 4) {
+                __builtin_nontemporal_store((uint16_t)wout, reinterpret_cast<uint16_t *>(reduced_out) + v);
+            } else {
+                uint8_t *b = reinterpret_cast<uint8_t *>(reduced_out) + (v << 1);
+                b[0] = (uint8_t)wout;
+                if (nvalid == 3) b[1] = (uint8_t)(wout >> 8);
+            }
+        }
+    }
+    if (deq_out) {
+        const float nrm = *norm;
+        const float c = (nrm > 0.0f && nrm <= 3.402823466e+38f) ? nrm / deq_div : 0.0f;   // norm * n' / (K s)
+        if (nvalid == 4) {
+            const f32x4 t = {(float)st[0][0] * c, (float)st[0][1] * c, (float)st[0][2] * c, (float)st[0][3] * c};
+            __builtin_nontemporal_store(t, reinterpret_cast<f32x4 *>(deq_out) + v);
+        } else {
+            for (int i = 0; i < nvalid; i++) deq_out[(v << 2) + i] = (float)st[0][i] * c;
+        }
+    }
+}
+
+}  // namespace gq
+
+using namespace gq;
+
+extern "C" {
+
+gq_status gq_exp_reduce(const void *const *levels, int K, int64_t d, const gq_params *p, int64_t index_base,
+                        const float *norm, void *reduced_out, float *dequant_out, void *hip_stream)
+{
+    gq_status st = check_params(p, false, false);
+    if (st != GQ_OK) return st;
+    if (p->scheme != GQ_EXP) return GQ_ERR_UNSUPPORTED;
+    if (!levels || K < 1 || K > GQ_MAX_WORKERS || d < 0 || index_base < 0 || (index_base & 3) != 0) return GQ_ERR_INVALID_ARG;
+    if (!reduced_out && !dequant_out) return GQ_ERR_INVALID_ARG;
+    if (dequant_out && !aligned(norm, 4)) return GQ_ERR_INVALID_ARG;
+    LevelCPtrs Lv;
+    for (int i = 0; i < K; i++) {
+        if (d > 0 && !aligned(levels[i], 16)) return GQ_ERR_INVALID_ARG;
+        Lv.lv[i] = levels[i];
+        Lv.sp[i] = nullptr;
+    }
+    if (d > 0 && ((reduced_out && !aligned(reduced_out, 16)) || (dequant_out && !aligned(dequant_out, 16)))) return GQ_ERR_INVALID_ARG;
+    if (d == 0) return GQ_OK;
+    const int64_t nvec = (d + 3) / 4;
+    const int64_t blocks = (nvec + kReduceBlock - 1) / kReduceBlock;
+    if (!grid_fits(blocks)) return GQ_ERR_INVALID_ARG;
+    const dim3 grid((unsigned)blocks), block(kReduceBlock);
+    const uint64_t call_base = (uint64_t)index_base / 4u;
+    const bool one_stretch = ((call_base & 0xFFFFFFFFull) + (uint64_t)(blocks * kReduceBlock)) <= ((uint64_t)1 << 32);
+    hipStream_t s = (hipStream_t)hip_stream;
+    int npad = 1;
+    while (npad < K) npad <<= 1;
+#define GQ_RED(N)                                                                                              \
+    do {                                                                                                       \
+        if (one_stretch) hipLaunchKernelGGL((exp_reduce_kernel<N, true>), grid, block, 0, s, Lv, K, d, p->s, p->seed, \
+                                            call_base, norm, reduced_out, dequant_out);                        \
+        else hipLaunchKernelGGL((exp_reduce_kernel<N, false>), grid, block, 0, s, Lv, K, d, p->s, p->seed,       \
+                                call_base, norm, reduced_out, dequant_out);                                    \
+    } while (0)
+    switch (npad) {
+    case 1: GQ_RED(1); break;
+    case 2: GQ_RED(2); break;
+    case 4: GQ_RED(4); break;
+    case 8: GQ_RED(8); break;
+    case 16: GQ_RED(16); break;
+    case 32: GQ_RED(32); break;
+    default: GQ_RED(64); break;
+    }
+#undef GQ_RED
+    return launched();
+}
+
+gq_status gq_avg_reduce(const void *const *levels, int K, int64_t d, const gq_params *p, int64_t index_base,
+                        const float *norm, void *reduced_out, float *dequant_out, void *hip_stream)
+{
+    gq_status st = check_params(p, true, false);
+    if (st != GQ_OK) return st;
+    if (p->scheme != GQ_LINEAR || (p->pack != GQ_PACK_I8 && p->pack != GQ_PACK_I4)) return GQ_ERR_UNSUPPORTED;
+    if (!levels || K < 1 || K > GQ_MAX_WORKERS || d < 0 || index_base < 0 || (index_base & 3) != 0) return GQ_ERR_INVALID_ARG;
+    if (!reduced_out && !dequant_out) return GQ_ERR_INVALID_ARG;
+    if (dequant_out && !aligned(norm, 4)) return GQ_ERR_INVALID_ARG;
+    LevelCPtrs Lv;
+    for (int i = 0; i < K; i++) {
+        if (d > 0 && !aligned(levels[i], 16)) return GQ_ERR_INVALID_ARG;
+        Lv.lv[i] = levels[i];
+        Lv.sp[i] = nullptr;
+    }
+    if (d > 0 && ((reduced_out && !aligned(reduced_out, 16)) || (dequant_out && !aligned(dequant_out, 16)))) return GQ_ERR_INVALID_ARG;
+    if (d == 0) return GQ_OK;
+    const int64_t nvec = (d + 3) / 4;
+    const int64_t blocks = (nvec + kReduceBlock - 1) / kReduceBlock;
+    if (!grid_fits(blocks)) return GQ_ERR_INVALID_ARG;
+    const dim3 grid((unsigned)blocks), block(kReduceBlock);
+    const uint64_t call_base = (uint64_t)index_base / 4u;
+    const bool one_stretch = ((call_base & 0xFFFFFFFFull) + (uint64_t)(blocks * kReduceBlock)) <= ((uint64_t)1 << 32);
+    hipStream_t s = (hipStream_t)hip_stream;
+    int npad = 1;
+    while (npad < K) npad <<= 1;
+    const float div = (float)((int64_t)K * p->s) / (float)npad;          // exact: a power-of-two division
+    const bool nib = p->pack == GQ_PACK_I4;
+#define GQ_AVG3(N, NB, UH) hipLaunchKernelGGL((avg_reduce_kernel<N, NB, UH>), grid, block, 0, s, Lv, K, d, p->seed, \
+                                              call_base, norm, div, reduced_out, dequant_out)
+#define GQ_AVG(N)                                                                              \
+    do {                                                                                       \
+        if (nib) { if (one_stretch) GQ_AVG3(N, true, true); else GQ_AVG3(N, true, false); }    \
+        else     { if (one_stretch) GQ_AVG3(N, false, true); else GQ_AVG3(N, false, false); }  \
+    } while (0)
+    switch (npad) {
+    case 1: GQ_AVG(1); break;
+    case 2: GQ_AVG(2); break;
+    case 4: GQ_AVG(4); break;
+    case 8: GQ_AVG(8); break;
+    case 16: GQ_AVG(16); break;
+    case 32: GQ_AVG(32); break;
+    default: GQ_AVG(64); break;
+    }
+#undef GQ_AVG
+#undef GQ_AVG3
+    return launched();
+}
+
+}  // extern "C"

@@ -1,0 +1,243 @@
+// Algorithm 1 lines 6-8 on MI355X (gfx950): compaction of non-zero codes and the sum of the K lists.
+// Contracts: include/gqsgd.h.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "gqsgd.h"
+#include "gq_device.hpp"
+#include "gq_host.hpp"
+
+namespace gq {
+
+// =============================================================================================
+// Algorithm 1 lines 6-8, the sparse branch.  Sender side: the (index, code) pairs of a worker's
+// non-zero int8 codes in increasing index order, by a count pass, a one-block scan of the block
+// counts and a write pass that ranks the non-zeros inside a block with wave scans.  Receiver side:
+// the K lists are added into a dense int32 sum with integer atomics (exact, order-free).
+// =============================================================================================
+constexpr int kCompactBlock = 256;
+constexpr int kCompactTile = kCompactBlock * 16;        // codes per block: one 128-bit load per thread
+constexpr int kScanBlock = 1024;
+
+__device__ __forceinline__ uint32_t nonzero_bytes(uint32_t x)    // 0x80 in every byte of x that is not zero
+{
+    return (x | ((x & 0x7F7F7F7Fu) + 0x7F7F7F7Fu)) & 0x80808080u;
+}
+
+// the 16 codes of unit t (bytes 16t .. 16t+15), zeros past the end of the buffer
+__device__ __forceinline__ u32x4 load_code_unit(const uint8_t *lv, int64_t t, int64_t d)
+{
+    const int64_t first = t << 4;
+    if (first + 16 <= d) return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(lv) + t);
+    uint32_t q[4] = {0u, 0u, 0u, 0u};
+    for (int i = 0; i < 16 && first + i < d; i++) q[i >> 2] |= (uint32_t)lv[first + i] << (8 * (i & 3));
+    return u32x4{q[0], q[1], q[2], q[3]};
+}
+
+__device__ __forceinline__ uint32_t count_unit(const u32x4 &c)
+{
+    return (uint32_t)(__builtin_popcount(nonzero_bytes(c.x)) + __builtin_popcount(nonzero_bytes(c.y)) +
+                      __builtin_popcount(nonzero_bytes(c.z)) + __builtin_popcount(nonzero_bytes(c.w)));
+}
+
+// Exclusive prefix sum of one value per thread over the block; every thread must call it.
+// `total` receives the block's sum.  sh must hold BLOCK/64 words.
+template <int BLOCK>
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *sh, uint32_t *total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t incl = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t t = (uint32_t)__shfl_up((int)incl, off, 64);
+        if (lane >= off) incl += t;
+    }
+    if (lane == 63) sh[wave] = incl;
+    __syncthreads();
+    uint32_t base = 0, sum = 0;
+    for (int i = 0; i < BLOCK / 64; i++) {
+        if (i < wave) base += sh[i];
+        sum += sh[i];
+    }
+    __syncthreads();
+    *total = sum;
+    return base + incl - v;
+}
+
+__global__ void __launch_bounds__(kCompactBlock)
+compact_count_kernel(const uint8_t *__restrict__ lv, int64_t d, uint32_t *__restrict__ block_counts)
+{
+    __shared__ uint32_t sh[kCompactBlock / 64];
+    const int64_t t = (int64_t)blockIdx.x * kCompactBlock + threadIdx.x;
+    const uint32_t c = count_unit(load_code_unit(lv, t, d));
+    uint32_t total;
+    block_exclusive_scan<kCompactBlock>(c, sh, &total);
+    if (threadIdx.x == 0) block_counts[blockIdx.x] = total;
+}
+
+// One block: counts[0..n) -> exclusive offsets in place; the grand total goes to *total_out.
+__global__ void __launch_bounds__(kScanBlock)
+compact_scan_kernel(uint32_t *__restrict__ counts, int64_t n, uint64_t *__restrict__ total_out)
+{
+    __shared__ uint32_t sh[kScanBlock / 64];
+    const int64_t per = (n + kScanBlock - 1) / kScanBlock;
+    const int64_t lo = (int64_t)threadIdx.x * per, hi = lo + per < n ? lo + per : n;
+    uint32_t mine = 0;
+    for (int64_t i = lo; i < hi; i++) mine += counts[i];
+    uint32_t total;
+    uint32_t run = block_exclusive_scan<kScanBlock>(mine, sh, &total);
+    for (int64_t i = lo; i < hi; i++) {
+        const uint32_t c = counts[i];
+        counts[i] = run;
+        run += c;
+    }
+    if (threadIdx.x == 0) *total_out = (uint64_t)total;
+}
+
+__global__ void __launch_bounds__(kCompactBlock)
+compact_write_kernel(const uint8_t *__restrict__ lv, int64_t d, const uint32_t *__restrict__ block_offsets,
+                     uint32_t *__restrict__ indices_out, int8_t *__restrict__ values_out, int64_t capacity)
+{
+    __shared__ uint32_t sh[kCompactBlock / 64];
+    const int64_t t = (int64_t)blockIdx.x * kCompactBlock + threadIdx.x;
+    const u32x4 c = load_code_unit(lv, t, d);
+    uint32_t total;
+    const uint32_t rank = block_exclusive_scan<kCompactBlock>(count_unit(c), sh, &total);
+    int64_t pos = (int64_t)block_offsets[blockIdx.x] + rank;
+    const uint32_t w[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+        const uint32_t b = (w[i >> 2] >> (8 * (i & 3))) & 255u;
+        if (b != 0u) {
+            if (pos < capacity) {
+                indices_out[pos] = (uint32_t)((t << 4) + i);
+                values_out[pos] = (int8_t)b;
+            }
+            pos++;
+        }
+    }
+}
+
+__global__ void __launch_bounds__(kBlock) fill_zero_kernel(int *__restrict__ p, int64_t n)
+{
+    const int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t nfull = n >> 2;
+    if (v < nfull) {
+        const i32x4 z = {0, 0, 0, 0};
+        reinterpret_cast<i32x4 *>(p)[v] = z;
+    } else if (v == nfull) {
+        for (int64_t i = nfull << 2; i < n; i++) p[i] = 0;
+    }
+}
+
+struct SparseLists {
+    const uint32_t *idx[kMaxWorkers];
+    const int8_t *val[kMaxWorkers];
+    const uint64_t *cnt[kMaxWorkers];
+    int64_t cap[kMaxWorkers];
+};
+
+template <int SCHEME>
+__global__ void __launch_bounds__(kBlock) sparse_scatter_kernel(SparseLists S, int64_t d, int *__restrict__ agg)
+{
+    const int w = blockIdx.y;
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const uint64_t have = *S.cnt[w];
+    const int64_t n = have < (uint64_t)S.cap[w] ? (int64_t)have : S.cap[w];
+    if (i >= n) return;
+    const uint32_t j = S.idx[w][i];
+    if ((int64_t)j >= d) return;                            // an index outside the buffer is ignored
+    const int q = S.val[w][i];
+    int val = q;
+    if (SCHEME == 1) {
+        const int mag = (int)((1u << abs(q)) >> 1);
+        val = q < 0 ? -mag : mag;
+    }
+    atomicAdd(agg + j, val);
+}
+
+}  // namespace gq
+
+using namespace gq;
+
+extern "C" {
+
+size_t gq_compact_workspace_bytes(int64_t d)
+{
+    if (d < 0 || d > 0xFFFFFFFFLL) return 0;
+    const int64_t blocks = (d + kCompactTile - 1) / kCompactTile;
+    return (size_t)(blocks > 0 ? blocks : 1) * sizeof(uint32_t);
+}
+
+gq_status gq_compact(const void *levels, int64_t d, const gq_params *p, uint32_t *indices_out, int8_t *values_out,
+                     int64_t capacity, uint64_t *count_out, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    const gq_status st = check_params(p, true, false);
+    if (st != GQ_OK) return st;
+    if (p->pack != GQ_PACK_I8) return GQ_ERR_UNSUPPORTED;
+    if (d < 0 || d > 0xFFFFFFFFLL || capacity < 0) return GQ_ERR_INVALID_ARG;
+    if (!aligned(count_out, 8)) return GQ_ERR_INVALID_ARG;
+    if (d > 0 && !aligned(levels, 16)) return GQ_ERR_INVALID_ARG;
+    if (capacity > 0 && (!aligned(indices_out, 4) || !values_out)) return GQ_ERR_INVALID_ARG;
+    if (!workspace || workspace_bytes < gq_compact_workspace_bytes(d)) return GQ_ERR_WORKSPACE;
+    if (!aligned(workspace, 4)) return GQ_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)hip_stream;
+    uint32_t *counts = reinterpret_cast<uint32_t *>(workspace);
+    const int64_t blocks = (d + kCompactTile - 1) / kCompactTile;
+    if (!grid_fits(blocks)) return GQ_ERR_INVALID_ARG;
+    const uint8_t *lv = reinterpret_cast<const uint8_t *>(levels);
+    if (blocks > 0) {
+        hipLaunchKernelGGL(compact_count_kernel, dim3((unsigned)blocks), dim3(kCompactBlock), 0, s, lv, d, counts);
+        if (launched() != GQ_OK) return GQ_ERR_DEVICE;
+    }
+    hipLaunchKernelGGL(compact_scan_kernel, dim3(1), dim3(kScanBlock), 0, s, counts, blocks, count_out);
+    if (launched() != GQ_OK) return GQ_ERR_DEVICE;
+    if (blocks > 0) {
+        hipLaunchKernelGGL(compact_write_kernel, dim3((unsigned)blocks), dim3(kCompactBlock), 0, s, lv, d, counts,
+                           indices_out, values_out, capacity);
+        if (launched() != GQ_OK) return GQ_ERR_DEVICE;
+    }
+    return GQ_OK;
+}
+
+gq_status gq_sparse_aggregate(const uint32_t *const *indices, const int8_t *const *values,
+                              const uint64_t *const *counts, const int64_t *capacities, int K, int64_t d,
+                              const gq_params *p, void *agg_out, void *hip_stream)
+{
+    gq_status st = check_params(p, false, true);
+    if (st != GQ_OK) return st;
+    if (p->agg != GQ_AGG_I32) return GQ_ERR_UNSUPPORTED;
+    if (!indices || !values || !counts || !capacities || K < 1 || K > GQ_MAX_WORKERS || d < 0 || d > 0xFFFFFFFFLL)
+        return GQ_ERR_INVALID_ARG;
+    st = gq_check_width(p, K);
+    if (st != GQ_OK) return st;
+    SparseLists S;
+    int64_t maxcap = 0;
+    for (int i = 0; i < K; i++) {
+        if (capacities[i] < 0 || !aligned(counts[i], 8)) return GQ_ERR_INVALID_ARG;
+        if (capacities[i] > 0 && (!aligned(indices[i], 4) || !values[i])) return GQ_ERR_INVALID_ARG;
+        S.idx[i] = indices[i];
+        S.val[i] = values[i];
+        S.cnt[i] = counts[i];
+        S.cap[i] = capacities[i];
+        if (capacities[i] > maxcap) maxcap = capacities[i];
+    }
+    if (d > 0 && !aligned(agg_out, 16)) return GQ_ERR_INVALID_ARG;
+    if (d == 0) return GQ_OK;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const int64_t zblocks = ((d + 3) / 4 + kBlock - 1) / kBlock;
+    const int64_t sblocks = (maxcap + kBlock - 1) / kBlock;
+    if (!grid_fits(zblocks) || !grid_fits(sblocks)) return GQ_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)zblocks), dim3(kBlock), 0, s, (int *)agg_out, d);
+    if (launched() != GQ_OK) return GQ_ERR_DEVICE;
+    if (sblocks > 0) {
+        const dim3 grid((unsigned)sblocks, (unsigned)K);
+        if (p->scheme == GQ_LINEAR) hipLaunchKernelGGL(sparse_scatter_kernel<0>, grid, dim3(kBlock), 0, s, S, d, (int *)agg_out);
+        else hipLaunchKernelGGL(sparse_scatter_kernel<1>, grid, dim3(kBlock), 0, s, S, d, (int *)agg_out);
+        if (launched() != GQ_OK) return GQ_ERR_DEVICE;
+    }
+    return GQ_OK;
+}
+
+}  // extern "C"
