@@ -270,12 +270,22 @@ def main():
         torch.cuda.synchronize()
         line["calibration_copy_bytes_each_way"] = src.numel() * 4
     if not args.no_cpu_baseline:
-        nf = np.float32(norm.item())
+        # the oracle is given a norm that does not come from the library: torch's reduction of the same buffers
+        if kind == gq.GQ_NORM_LINF:
+            nf = np.float32(max(float(x.abs().max()) for x in xs))
+        else:
+            nf = np.float32(np.sqrt(sum(float((x.double() * x.double()).sum()) for x in xs)))
         base, parts, cuts = cpu_baseline(xs, nf, scheme, s, SI.QUANT_SEED, args.cpu_sample, 4.0 * K + 4.0)
         # the sample doubles as a parity check of the timed launch
         if bucket:
             base["matches_gpu"] = None          # the bucketed step stores the mean only
         else:
+            # (the max norm is exact, so the timed launch used the same norm; under an L2 norm the launch is
+            #  repeated with the oracle's norm before comparing)
+            if np.float32(norm.item()) != nf:
+                norm.fill_(float(nf))
+                gq.fused_quantize_aggregate(xs, norm, params, 0, agg, None)
+                torch.cuda.synchronize()
             got = agg[:cuts[-1][1]].cpu().numpy().astype(np.int64)
             base["matches_gpu"] = bool(all(np.array_equal(got[lo:hi], p) for (lo, hi), p in zip(cuts, parts)))
         line["cpu_baseline"] = base

@@ -136,7 +136,8 @@ def test_workload_c5_bucketed_fused_quantize_aggregate_dequantize():
     torch.cuda.synchronize()
     want_norm = torch_norm(xs, "l2")
     assert abs(float(norm_t.item()) - want_norm) <= RTOL * want_norm and flags.item() == 0
-    nf = np.float32(norm_t.item())      # a binary32 value within 1e-5 of the exact norm; both sides use it
+    nf = np.float32(want_norm)          # torch's binary64 norm rounded once: the norm both sides are given
+    norm_t.fill_(float(nf))
     p = gq.make_params(gq.GQ_LINEAR, s, gq.GQ_PACK_U4_SIGNPLANE, gq.GQ_AGG_I32, seed=SI.QUANT_SEED)
     out = torch.empty(d, device=DEV)
     nb = SI.num_buckets(d, bucket)
