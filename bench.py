@@ -7,7 +7,7 @@ global_norm -> fused quantize+aggregate (quantisation of all workers and the int
 registers) -> dequantize.  HIP events on the launch stream bracket the timed steps and each call
 inside them.  One JSON line is printed:
 
-  value      the metric the benchmark spec names: algorithmic GB/s of the fused quantize+aggregate call
+  value      the headline metric: algorithmic GB/s of the fused quantize+aggregate call
              (4K bytes read + 4 bytes written per output coordinate, divided by the call's mean
              duration inside the timed steps), inputs resident in HBM
   roofline   the same kernel against MI355X's 8 TB/s HBM peak; `traffic` is the HBM byte count per
