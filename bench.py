@@ -153,7 +153,7 @@ def time_rows(gq, torch, xs, norm, params, cfg, args):
         tot = float(sum(nnz))
         rows["compact_xK"] = timed(compact_all, 2.0 * K * d + 5.0 * tot)
         if aggf == gq.GQ_AGG_I32:
-            rows["sparse_aggregate"] = timed(lambda: gq.sparse_aggregate(idxs, vals, cnts, d, p, agg), 4.0 * d + 13.0 * tot)
+            rows["sparse_aggregate"] = timed(lambda: gq.sparse_aggregate(idxs, vals, cnts, d, p, agg), 4.0 * d + 5.0 * tot)
         rows["nonzero_fraction"] = tot / (float(K) * d)
     rows["formats"] = {"pack": cfg["pack"], "agg": cfg["agg"]}
     return rows

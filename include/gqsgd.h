@@ -204,7 +204,7 @@ gq_status gq_compact(const void *levels, int64_t d, const gq_params *p /* host *
 
 /* Receiver side of the sparse branch: the dense integer sum A_j of the K workers' lists, equal to what
  * gq_int_aggregate forms from the dense codes.
- *   indices, values  host arrays of K device lists as written by gq_compact
+ *   indices, values  host arrays of K device lists as written by gq_compact (indices strictly increasing)
  *   counts           host array of K device uint64[1] (read on the device; min(count, capacity) entries are used)
  *   capacities       host array of K list capacities
  *   agg_out          device int32[d] (p->agg must be GQ_AGG_I32), fully overwritten

@@ -14,7 +14,7 @@ namespace gq {
 // Algorithm 1 lines 6-8, the sparse branch.  Sender side: the (index, code) pairs of a worker's
 // non-zero int8 codes in increasing index order, by a count pass, a one-block scan of the block
 // counts and a write pass that ranks the non-zeros inside a block with wave scans.  Receiver side:
-// the K lists are added into a dense int32 sum with integer atomics (exact, order-free).
+// the K sorted lists are merged tile by tile into the dense int32 sum.
 // =============================================================================================
 constexpr int kCompactBlock = 256;
 constexpr int kCompactTile = kCompactBlock * 16;        // codes per block: one 128-bit load per thread
@@ -95,39 +95,36 @@ compact_scan_kernel(uint32_t *__restrict__ counts, int64_t n, uint64_t *__restri
     if (threadIdx.x == 0) *total_out = (uint64_t)total;
 }
 
+// The block's pairs are first ranked into LDS (a block never holds more than kCompactTile of them) and then
+// copied out with consecutive lanes writing consecutive list entries.
 __global__ void __launch_bounds__(kCompactBlock)
 compact_write_kernel(const uint8_t *__restrict__ lv, int64_t d, const uint32_t *__restrict__ block_offsets,
                      uint32_t *__restrict__ indices_out, int8_t *__restrict__ values_out, int64_t capacity)
 {
     __shared__ uint32_t sh[kCompactBlock / 64];
+    __shared__ uint32_t s_idx[kCompactTile];
+    __shared__ int8_t s_val[kCompactTile];
     const int64_t t = (int64_t)blockIdx.x * kCompactBlock + threadIdx.x;
     const u32x4 c = load_code_unit(lv, t, d);
     uint32_t total;
-    const uint32_t rank = block_exclusive_scan<kCompactBlock>(count_unit(c), sh, &total);
-    int64_t pos = (int64_t)block_offsets[blockIdx.x] + rank;
+    uint32_t rank = block_exclusive_scan<kCompactBlock>(count_unit(c), sh, &total);
     const uint32_t w[4] = {c.x, c.y, c.z, c.w};
 #pragma unroll
     for (int i = 0; i < 16; i++) {
         const uint32_t b = (w[i >> 2] >> (8 * (i & 3))) & 255u;
         if (b != 0u) {
-            if (pos < capacity) {
-                indices_out[pos] = (uint32_t)((t << 4) + i);
-                values_out[pos] = (int8_t)b;
-            }
-            pos++;
+            s_idx[rank] = (uint32_t)((t << 4) + i);
+            s_val[rank] = (int8_t)b;
+            rank++;
         }
     }
-}
-
-__global__ void __launch_bounds__(kBlock) fill_zero_kernel(int *__restrict__ p, int64_t n)
-{
-    const int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    const int64_t nfull = n >> 2;
-    if (v < nfull) {
-        const i32x4 z = {0, 0, 0, 0};
-        reinterpret_cast<i32x4 *>(p)[v] = z;
-    } else if (v == nfull) {
-        for (int64_t i = nfull << 2; i < n; i++) p[i] = 0;
+    __syncthreads();
+    const int64_t base = (int64_t)block_offsets[blockIdx.x];
+    for (uint32_t e = threadIdx.x; e < total; e += kCompactBlock) {
+        if (base + e < capacity) {
+            indices_out[base + e] = s_idx[e];
+            values_out[base + e] = s_val[e];
+        }
     }
 }
 
@@ -138,23 +135,56 @@ struct SparseLists {
     int64_t cap[kMaxWorkers];
 };
 
+// Receiver side.  A block owns a tile of kSparseTile coordinates: two threads per worker find, by binary
+// search in the sorted index list, the entries that fall into the tile; the block adds their integer
+// values into an LDS copy of the tile (LDS atomics) and writes the tile with 128-bit stores.  No global
+// atomics and no separate zero fill: every output word is written exactly once.
+constexpr int kSparseTile = 4096;
+
 template <int SCHEME>
-__global__ void __launch_bounds__(kBlock) sparse_scatter_kernel(SparseLists S, int64_t d, int *__restrict__ agg)
+__global__ void __launch_bounds__(kBlock) sparse_tile_kernel(SparseLists S, int K, int64_t d, int *__restrict__ agg)
 {
-    const int w = blockIdx.y;
-    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    const uint64_t have = *S.cnt[w];
-    const int64_t n = have < (uint64_t)S.cap[w] ? (int64_t)have : S.cap[w];
-    if (i >= n) return;
-    const uint32_t j = S.idx[w][i];
-    if ((int64_t)j >= d) return;                            // an index outside the buffer is ignored
-    const int q = S.val[w][i];
-    int val = q;
-    if (SCHEME == 1) {
-        const int mag = (int)((1u << abs(q)) >> 1);
-        val = q < 0 ? -mag : mag;
+    __shared__ int tile[kSparseTile];
+    __shared__ int64_t range[2 * kMaxWorkers];
+    const int64_t lo = (int64_t)blockIdx.x * kSparseTile;
+    const int64_t hi = lo + kSparseTile < d ? lo + kSparseTile : d;
+    for (int i = threadIdx.x; i < kSparseTile; i += kBlock) tile[i] = 0;
+    if ((int)threadIdx.x < 2 * K) {
+        const int w = threadIdx.x >> 1;
+        const int64_t key = (threadIdx.x & 1) ? hi : lo;
+        const uint64_t have = *S.cnt[w];
+        const int64_t n = have < (uint64_t)S.cap[w] ? (int64_t)have : S.cap[w];
+        int64_t a = 0, b = n;                                  // first entry whose index is >= key
+        while (a < b) {
+            const int64_t mid = (a + b) >> 1;
+            if ((int64_t)S.idx[w][mid] < key) a = mid + 1; else b = mid;
+        }
+        range[threadIdx.x] = a;
     }
-    atomicAdd(agg + j, val);
+    __syncthreads();
+    for (int w = 0; w < K; w++) {
+        const int64_t end = range[2 * w + 1];
+        for (int64_t e = range[2 * w] + threadIdx.x; e < end; e += kBlock) {
+            const int64_t j = (int64_t)S.idx[w][e] - lo;
+            const int q = S.val[w][e];
+            int val = q;
+            if (SCHEME == 1) {
+                const int mag = (int)((1u << abs(q)) >> 1);
+                val = q < 0 ? -mag : mag;
+            }
+            if (j >= 0 && j < kSparseTile) atomicAdd(&tile[j], val);   // always true for a sorted list
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x * 4; i < kSparseTile; i += kBlock * 4) {
+        const int64_t c = lo + i;
+        if (c + 4 <= d) {
+            const i32x4 o = {tile[i], tile[i + 1], tile[i + 2], tile[i + 3]};
+            __builtin_nontemporal_store(o, reinterpret_cast<i32x4 *>(agg + c));
+        } else {
+            for (int t = 0; t < 4 && c + t < d; t++) agg[c + t] = tile[i + t];
+        }
+    }
 }
 
 }  // namespace gq
@@ -213,7 +243,6 @@ gq_status gq_sparse_aggregate(const uint32_t *const *indices, const int8_t *cons
     st = gq_check_width(p, K);
     if (st != GQ_OK) return st;
     SparseLists S;
-    int64_t maxcap = 0;
     for (int i = 0; i < K; i++) {
         if (capacities[i] < 0 || !aligned(counts[i], 8)) return GQ_ERR_INVALID_ARG;
         if (capacities[i] > 0 && (!aligned(indices[i], 4) || !values[i])) return GQ_ERR_INVALID_ARG;
@@ -221,22 +250,16 @@ gq_status gq_sparse_aggregate(const uint32_t *const *indices, const int8_t *cons
         S.val[i] = values[i];
         S.cnt[i] = counts[i];
         S.cap[i] = capacities[i];
-        if (capacities[i] > maxcap) maxcap = capacities[i];
     }
     if (d > 0 && !aligned(agg_out, 16)) return GQ_ERR_INVALID_ARG;
     if (d == 0) return GQ_OK;
     hipStream_t s = (hipStream_t)hip_stream;
-    const int64_t zblocks = ((d + 3) / 4 + kBlock - 1) / kBlock;
-    const int64_t sblocks = (maxcap + kBlock - 1) / kBlock;
-    if (!grid_fits(zblocks) || !grid_fits(sblocks)) return GQ_ERR_INVALID_ARG;
-    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)zblocks), dim3(kBlock), 0, s, (int *)agg_out, d);
+    const int64_t blocks = (d + kSparseTile - 1) / kSparseTile;
+    if (!grid_fits(blocks)) return GQ_ERR_INVALID_ARG;
+    const dim3 grid((unsigned)blocks);
+    if (p->scheme == GQ_LINEAR) hipLaunchKernelGGL(sparse_tile_kernel<0>, grid, dim3(kBlock), 0, s, S, K, d, (int *)agg_out);
+    else hipLaunchKernelGGL(sparse_tile_kernel<1>, grid, dim3(kBlock), 0, s, S, K, d, (int *)agg_out);
     if (launched() != GQ_OK) return GQ_ERR_DEVICE;
-    if (sblocks > 0) {
-        const dim3 grid((unsigned)sblocks, (unsigned)K);
-        if (p->scheme == GQ_LINEAR) hipLaunchKernelGGL(sparse_scatter_kernel<0>, grid, dim3(kBlock), 0, s, S, d, (int *)agg_out);
-        else hipLaunchKernelGGL(sparse_scatter_kernel<1>, grid, dim3(kBlock), 0, s, S, d, (int *)agg_out);
-        if (launched() != GQ_OK) return GQ_ERR_DEVICE;
-    }
     return GQ_OK;
 }
 
