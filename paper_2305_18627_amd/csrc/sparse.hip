@@ -77,22 +77,22 @@ compact_count_kernel(const uint8_t *__restrict__ lv, int64_t d, uint32_t *__rest
 }
 
 // One block: counts[0..n) -> exclusive offsets in place; the grand total goes to *total_out.
+// The counts are taken kScanBlock at a time with consecutive lanes on consecutive words; the running
+// total is carried from one round to the next.
 __global__ void __launch_bounds__(kScanBlock)
 compact_scan_kernel(uint32_t *__restrict__ counts, int64_t n, uint64_t *__restrict__ total_out)
 {
     __shared__ uint32_t sh[kScanBlock / 64];
-    const int64_t per = (n + kScanBlock - 1) / kScanBlock;
-    const int64_t lo = (int64_t)threadIdx.x * per, hi = lo + per < n ? lo + per : n;
-    uint32_t mine = 0;
-    for (int64_t i = lo; i < hi; i++) mine += counts[i];
-    uint32_t total;
-    uint32_t run = block_exclusive_scan<kScanBlock>(mine, sh, &total);
-    for (int64_t i = lo; i < hi; i++) {
-        const uint32_t c = counts[i];
-        counts[i] = run;
-        run += c;
+    uint32_t carry = 0;
+    for (int64_t base = 0; base < n; base += kScanBlock) {
+        const int64_t i = base + threadIdx.x;
+        const uint32_t c = i < n ? counts[i] : 0u;
+        uint32_t total;
+        const uint32_t excl = block_exclusive_scan<kScanBlock>(c, sh, &total);
+        if (i < n) counts[i] = carry + excl;
+        carry += total;
     }
-    if (threadIdx.x == 0) *total_out = (uint64_t)total;
+    if (threadIdx.x == 0) *total_out = (uint64_t)carry;
 }
 
 // The block's pairs are first ranked into LDS (a block never holds more than kCompactTile of them) and then
