@@ -23,6 +23,8 @@ namespace gq {
 //   KT          compile-time worker count (fully unrolled, K loads in flight), 0 = run-time K
 //   LEVELS      also store every worker's packed codes
 //   UNIFORM_HI  the high word of the Philox call index is the same for the whole launch
+//   WINDOWS     keep few loads in flight per lane and store the sum only inside chip-wide time
+//               windows (see below)
 // =============================================================================================
 __device__ __forceinline__ f32x4 load_coords(const float *x, int64_t v, int nvalid)
 {
@@ -89,22 +91,41 @@ template <> struct Acc<0> {
     float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
     __device__ __forceinline__ void add(float f0, float f1, float f2, float f3) { a0 += f0; a1 += f1; a2 += f2; a3 += f3; }
     __device__ __forceinline__ i32x4 get() const { return i32x4{(int)a0, (int)a1, (int)a2, (int)a3}; }
+    __device__ __forceinline__ void pin() { asm volatile("" : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3) : : "memory"); }
 };
 template <> struct Acc<1> {
     int a0 = 0, a1 = 0, a2 = 0, a3 = 0;
     __device__ __forceinline__ void add(float f0, float f1, float f2, float f3) { a0 += (int)f0; a1 += (int)f1; a2 += (int)f2; a3 += (int)f3; }
     __device__ __forceinline__ i32x4 get() const { return i32x4{a0, a1, a2, a3}; }
+    __device__ __forceinline__ void pin() { asm volatile("" : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3) : : "memory"); }
 };
+
+// Write windows.  The kernel reads 4K bytes and writes 4 bytes per coordinate.  With every wave storing
+// whenever it happens to finish, HBM sees writes sprinkled evenly into the read stream and pays a bus
+// turnaround for each; measured on MI355X this mix runs at 5.8-6.1 TB/s while the same reads alone
+// reach 7 TB/s.  With WINDOWS a wave that has finished its sum waits (sleeping) until the constant
+// 100 MHz counter, which all compute units share, enters the first tenth of a period of
+// kWindowTicksPerWorker * K ticks, and stores then: the chip alternates between a long stretch of pure
+// reads and a short burst of writes (6.3-6.5 TB/s for K >= 12).  The period is the time one
+// generation of resident waves needs for its K loads, so a wave waits for about one window, not more.
+// The wait is bounded (at most 4096 polls) and touches no memory, so it changes timing only.  For this
+// to work the loads of a lane must really stay few in flight: the accumulators are pinned after each
+// batch of four workers, which stops the compiler from hoisting all K loads to the top (it would
+// otherwise, and with every load issued up front the windows were measured to gain nothing).
+constexpr uint32_t kWindowTicksPerWorker = 62;    // ticks of the 100 MHz counter per worker and period
+constexpr int kWindowMinWorkers = 8;
+constexpr double kWindowMinLoads = 2.5e8;         // K * d from which the windows win (measured)
 
 // The launch covers the 4-coordinate vectors v0 <= v < vend of the buffers.  With UNIFORM_HI the
 // host guarantees that the Philox call index (call_base + v) does not cross a multiple of 2^32 inside
 // the launch, so the high counter word is a scalar: the first round and half of the second are then
 // shared by all lanes or all workers and leave the vector ALU.
-template <int SCHEME, int KT, bool LEVELS, bool UNIFORM_HI>
+template <int SCHEME, int KT, bool LEVELS, bool UNIFORM_HI, bool WINDOWS>
 __global__ void __launch_bounds__(kFusedBlock)
 quantize_aggregate_kernel(GradPtrs P, LevelPtrs L, int K, int64_t d, int64_t v0, int64_t vend, const float *__restrict__ norm, int s,
                           uint64_t seed, uint32_t worker0, uint64_t call_base, int pack,
-                          void *__restrict__ agg_out, int agg_fmt, float *__restrict__ deq_out, float deq_div)
+                          void *__restrict__ agg_out, int agg_fmt, float *__restrict__ deq_out, float deq_div,
+                          uint32_t win_period, uint32_t win_open)
 {
     const int64_t v = v0 + (int64_t)blockIdx.x * kFusedBlock + threadIdx.x;
     const int64_t nfull = d >> 2;
@@ -141,7 +162,7 @@ quantize_aggregate_kernel(GradPtrs P, LevelPtrs L, int K, int64_t d, int64_t v0,
         }
     };
     if (KT > 0) {
-        constexpr int kInFlight = KT > 16 ? 16 : (KT > 0 ? KT : 1);   // loads issued before the first is consumed
+        constexpr int kInFlight = WINDOWS ? (KT > 4 ? 4 : (KT > 0 ? KT : 1)) : (KT > 16 ? 16 : (KT > 0 ? KT : 1));   // loads issued before the first is consumed
 #pragma unroll
         for (int w0 = 0; w0 < KT; w0 += kInFlight) {
             f32x4 g[kInFlight];
@@ -155,6 +176,7 @@ quantize_aggregate_kernel(GradPtrs P, LevelPtrs L, int K, int64_t d, int64_t v0,
             }
 #pragma unroll
             for (int j = 0; j < kInFlight; j++) one_worker(w0 + j, g[j]);
+            if (WINDOWS) acc.pin();
         }
     } else {
         int w = 0;
@@ -167,6 +189,13 @@ quantize_aggregate_kernel(GradPtrs P, LevelPtrs L, int K, int64_t d, int64_t v0,
     }
     if (nvalid == 0) return;
 
+    if (WINDOWS) {
+        for (int it = 0; it < 4096; it++) {
+            const uint32_t t = (uint32_t)__builtin_amdgcn_s_memrealtime();
+            if ((t % win_period) < win_open) break;
+            __builtin_amdgcn_s_sleep(8);
+        }
+    }
     const i32x4 a = acc.get();
     if (agg_out) {
         if (agg_fmt == GQ_AGG_I32) {
@@ -258,19 +287,24 @@ static gq_status launch_quantize_aggregate(const GradPtrs &P, const LevelPtrs &L
     const uint64_t call_base = (uint64_t)index_base / 4u;
     const float div = dequant_divisor(p, K);
     const dim3 block(kFusedBlock);
-#define GQ_LAUNCH(KT, LV, UH, V0, COUNT)                                                                      \
+    // Write windows pay once a launch lasts many periods and a wave's K loads span about one period;
+    // below these sizes the wait for the next window costs more than the cleaner read/write mix gains.
+    const bool win = !levels && K >= kWindowMinWorkers && (double)K * (double)d >= kWindowMinLoads;
+    const uint32_t win_period = kWindowTicksPerWorker * (uint32_t)K;
+    const uint32_t win_open = win_period / 10u;
+#define GQ_LAUNCH(KT, LV, UH, WIN, V0, COUNT)                                                                      \
     do {                                                                                                      \
         const int64_t blocks_ = ((COUNT) + kFusedBlock - 1) / kFusedBlock;                                    \
         if (!grid_fits(blocks_)) return GQ_ERR_INVALID_ARG;                                                   \
-        hipLaunchKernelGGL((quantize_aggregate_kernel<SCHEME, KT, LV, UH>), dim3((unsigned)blocks_), block, 0, st, \
+        hipLaunchKernelGGL((quantize_aggregate_kernel<SCHEME, KT, LV, UH, WIN>), dim3((unsigned)blocks_), block, 0, st, \
                            P, L, K, d, (int64_t)(V0), (int64_t)(V0) + (int64_t)(COUNT), norm, p->s, p->seed, worker0, call_base, p->pack,       \
-                           agg_out, p->agg, deq_out, div);                                                    \
+                           agg_out, p->agg, deq_out, div, win_period, win_open);                                                    \
     } while (0)
     if (levels) {
         // storing codes: one launch; the scalar high word is used when the bucket does not cross 2^34
         const bool one_stretch = ((call_base & 0xFFFFFFFFull) + (uint64_t)nvec) <= ((uint64_t)1 << 32);
-        if (one_stretch) GQ_LAUNCH(0, true, true, 0, nvec);
-        else GQ_LAUNCH(0, true, false, 0, nvec);
+        if (one_stretch) GQ_LAUNCH(0, true, true, false, 0, nvec);
+        else GQ_LAUNCH(0, true, false, false, 0, nvec);
         return launched();
     }
     // One launch per stretch of vectors whose Philox call index shares its high 32 bits (a second
@@ -280,11 +314,19 @@ static gq_status launch_quantize_aggregate(const GradPtrs &P, const LevelPtrs &L
         const uint64_t first = call_base + (uint64_t)v0;
         const uint64_t room = ((uint64_t)1 << 32) - (first & 0xFFFFFFFFull);
         const int64_t count = (uint64_t)(nvec - v0) < room ? (nvec - v0) : (int64_t)room;
-        if (K == 4) GQ_LAUNCH(4, false, true, v0, count);
-        else if (K == 8) GQ_LAUNCH(8, false, true, v0, count);
-        else if (K == 16) GQ_LAUNCH(16, false, true, v0, count);
-        else if (K == 32) GQ_LAUNCH(32, false, true, v0, count);
-        else GQ_LAUNCH(0, false, true, v0, count);
+        if (win) {
+            if (K == 4) GQ_LAUNCH(4, false, true, true, v0, count);
+            else if (K == 8) GQ_LAUNCH(8, false, true, true, v0, count);
+            else if (K == 16) GQ_LAUNCH(16, false, true, true, v0, count);
+            else if (K == 32) GQ_LAUNCH(32, false, true, true, v0, count);
+            else GQ_LAUNCH(0, false, true, true, v0, count);
+        } else {
+            if (K == 4) GQ_LAUNCH(4, false, true, false, v0, count);
+            else if (K == 8) GQ_LAUNCH(8, false, true, false, v0, count);
+            else if (K == 16) GQ_LAUNCH(16, false, true, false, v0, count);
+            else if (K == 32) GQ_LAUNCH(32, false, true, false, v0, count);
+            else GQ_LAUNCH(0, false, true, false, v0, count);
+        }
         if (launched() != GQ_OK) return GQ_ERR_DEVICE;
         v0 += count;
     }

@@ -631,6 +631,37 @@ def check_windows(xs, agg, nf, scheme, s, seed, windows, width):
         assert np.array_equal(host(agg[lo:hi]).astype(np.int64), want), "window at %d" % lo
 
 
+@pytest.mark.parametrize("scheme,s,agg_fmt,K,d", [(0, 127, 0, 12, 21_000_003), (1, 7, 1, 24, 10_500_001),
+                                                  (0, 63, 0, 8, 31_300_002), (1, 12, 0, 19, 13_200_001)])
+def test_fused_large_launches_equal_small_buckets_and_oracle(scheme, s, agg_fmt, K, d):
+    # Launches with K * d >= 2.5e8 take the kernel variant that bounds its loads in flight and stores
+    # inside time windows; the same gradient cut into buckets below that size takes the plain variant.
+    # Both must give the same integers, and those of the oracle on sampled windows.
+    g = torch.Generator(device=DEV).manual_seed(1000 * K + s)
+    xs = [torch.randn(d, generator=g, device=DEV) * 1e-3 for _ in range(K)]
+    mx = max(float(x.abs().max()) for x in xs)
+    nf = np.float32(mx)
+    norm_t = dev_scalar(float(nf))
+    params = gq.make_params(scheme, s, 0, agg_fmt, seed=SI.QUANT_SEED + 1)
+    adt = torch.int16 if agg_fmt == 1 else torch.int32
+    whole = torch.full((d + 8,), 0x5A5A, dtype=adt, device=DEV)
+    whole_deq = torch.full((d + 8,), 7.0, device=DEV)
+    gq.fused_quantize_aggregate(xs, norm_t, params, 0, whole, whole_deq)
+    parts = torch.empty(d, dtype=adt, device=DEV)
+    parts_deq = torch.empty(d, device=DEV)
+    step = (int(2.0e8 / K) // 16) * 16
+    assert K * step < 2.5e8 <= K * d
+    for lo in range(0, d, step):
+        hi = min(d, lo + step)
+        gq.fused_quantize_aggregate([x[lo:hi] for x in xs], norm_t, params, lo, parts[lo:hi], parts_deq[lo:hi])
+    torch.cuda.synchronize()
+    assert torch.equal(whole[:d], parts) and torch.equal(whole_deq[:d], parts_deq)
+    assert bool((whole[d:] == 0x5A5A).all()) and bool((whole_deq[d:] == 7.0).all())
+    rng = np.random.default_rng(K)
+    wins = [0, d - (1 << 15)] + [int(v) for v in rng.integers(0, d - (1 << 15), 6)]
+    check_windows(xs, whole[:d], nf, scheme, s, params.seed, wins, 1 << 15)
+
+
 def test_workload_c1_full_parity():
     # d = 2^20, K = 4, L2 norm, linear s = 127, int8 codes, int32 sum: everything compared in full
     cfg = SI.CONFIGS["c1"]
