@@ -50,6 +50,13 @@
  *                z >= 1: z = 2^e * (1 + m/2^23); round up iff m + R >= 2^23: probability m/2^23 =
  *                (z - 2^e)/2^e exactly as Eq. (2) asks.   z < 1: m = z*2^23 rounded to nearest
  *                integer (ties to even); round up to the smallest level iff m + R >= 2^23.
+ *   - short draws (rng_bits = 16): the number of random bits per coordinate is a free choice under Eq. (2),
+ *     which fixes probabilities only.  With 16 bits per coordinate one Philox call serves the eight
+ *     coordinates 8c .. 8c+7: counter (lo32(g/8), hi32(g/8), worker, 0), word (g mod 8) / 2, low half for
+ *     even g, high half for odd g.  The 16 bits r16 take the place of the TOP half of the 32-bit word
+ *     (r = r16 * 2^16), and the two rules above are applied unchanged: P(up) is then met to 2^-16
+ *     (linear: count of r16 giving "up" is ceil(frac * 2^16) up to the binary32 rounding of U' and v;
+ *     exponential between two levels: floor(m / 2^7) of the 2^16 values).
  *   - Algorithm 2 (the paper's own aggregation for the exponential grid, kept beside the integer sum):
  *     values are prescaled by 1/(2 n'), n' = n rounded up to a power of two, so that a code k >= 1 of the
  *     exponential grid becomes the exponent e = s - k + 1 + log2(n') of sign * 2^-e, and e = 0 is zero
@@ -126,9 +133,29 @@ uint32_t gqo_random_word(uint64_t seed, uint32_t worker, uint64_t g)
     return out[g % 4u];
 }
 
-void gqo_random_words(uint64_t seed, uint32_t worker, uint64_t index_base, int64_t d, uint32_t *r)
+/* Short draws: the 16 random bits of (seed, worker, g), returned in the top half of a 32-bit word
+ * (r16 * 2^16) so that the rounding rules below apply unchanged.  One Philox call per 8 coordinates. */
+uint32_t gqo_random_word16(uint64_t seed, uint32_t worker, uint64_t g)
 {
-    for (int64_t j = 0; j < d; j++) r[j] = gqo_random_word(seed, worker, index_base + (uint64_t)j);
+    uint64_t call = g / 8u;
+    uint32_t ctr[4] = { (uint32_t)call, (uint32_t)(call >> 32), worker, 0u };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t out[4];
+    gqo_philox4x32(10, ctr, key, out);
+    uint32_t word = out[(g % 8u) / 2u];
+    uint32_t r16 = (g % 2u) ? (word >> 16) : (word & 0xFFFFu);
+    return r16 << 16;
+}
+
+/* The word that decides the rounding of coordinate g: rng_bits = 32 or 16 (anything else reads as 32). */
+uint32_t gqo_random_word_bits(uint64_t seed, uint32_t worker, uint64_t g, int rng_bits)
+{
+    return rng_bits == 16 ? gqo_random_word16(seed, worker, g) : gqo_random_word(seed, worker, g);
+}
+
+void gqo_random_words(uint64_t seed, uint32_t worker, uint64_t index_base, int64_t d, int rng_bits, uint32_t *r)
+{
+    for (int64_t j = 0; j < d; j++) r[j] = gqo_random_word_bits(seed, worker, index_base + (uint64_t)j, rng_bits);
 }
 
 /* ------------------------------------------------------------------------------------------
@@ -228,10 +255,10 @@ void gqo_quantize_with_words(const float *x, const uint32_t *r, int64_t d, float
 
 /* Algorithm 1 lines 2-5 for one worker. */
 void gqo_quantize(const float *x, int64_t d, float norm, int scheme, int s,
-                  uint64_t seed, uint32_t worker, uint64_t index_base, int32_t *q)
+                  uint64_t seed, uint32_t worker, uint64_t index_base, int rng_bits, int32_t *q)
 {
     for (int64_t j = 0; j < d; j++)
-        q[j] = gqo_code(scheme, x[j], norm, s, gqo_random_word(seed, worker, index_base + (uint64_t)j));
+        q[j] = gqo_code(scheme, x[j], norm, s, gqo_random_word_bits(seed, worker, index_base + (uint64_t)j, rng_bits));
 }
 
 /* Signed integer value that a signed code contributes to the sum. */
@@ -338,7 +365,7 @@ void gqo_unpack(const uint8_t *levels, const uint32_t *signplane, int64_t d, int
  * Returns 0, or -1 if memory for the K code vectors could not be had.
  * ------------------------------------------------------------------------------------------ */
 int gqo_quantize_aggregate(const float *const *x, int K, int64_t d, float norm, int scheme, int s,
-                           uint64_t seed, uint64_t index_base, int64_t *A)
+                           uint64_t seed, uint64_t index_base, int rng_bits, int64_t *A)
 {
     int32_t **q = (int32_t **)calloc((size_t)K, sizeof(int32_t *));
     if (!q) return -1;
@@ -346,7 +373,7 @@ int gqo_quantize_aggregate(const float *const *x, int K, int64_t d, float norm, 
     for (int i = 0; i < K; i++) {
         q[i] = (int32_t *)malloc((size_t)(d > 0 ? d : 1) * sizeof(int32_t));
         if (!q[i]) { rc = -1; break; }
-        gqo_quantize(x[i], d, norm, scheme, s, seed, (uint32_t)i, index_base, q[i]);
+        gqo_quantize(x[i], d, norm, scheme, s, seed, (uint32_t)i, index_base, rng_bits, q[i]);
     }
     if (rc == 0) gqo_aggregate((const int32_t *const *)q, K, d, scheme, A);
     for (int i = 0; i < K; i++) free(q[i]);

@@ -33,13 +33,13 @@ def _sig(name, res, *args):
 
 _philox = _sig("gqo_philox4x32", None, C.c_int, _u32p, _u32p, _u32p)
 _random_word = _sig("gqo_random_word", C.c_uint32, C.c_uint64, C.c_uint32, C.c_uint64)
-_random_words = _sig("gqo_random_words", None, C.c_uint64, C.c_uint32, C.c_uint64, C.c_int64, _u32p)
+_random_words = _sig("gqo_random_words", None, C.c_uint64, C.c_uint32, C.c_uint64, C.c_int64, C.c_int, _u32p)
 _global_norm = _sig("gqo_global_norm", C.c_int, C.POINTER(_f32p), C.c_int, C.c_int64, C.c_int, _f64p, _f32p)
 _code = _sig("gqo_code", C.c_int32, C.c_int, C.c_float, C.c_float, C.c_int, C.c_uint32)
 _quantize_with_words = _sig("gqo_quantize_with_words", None, _f32p, _u32p, C.c_int64, C.c_float,
                             C.c_int, C.c_int, _i32p)
 _quantize = _sig("gqo_quantize", None, _f32p, C.c_int64, C.c_float, C.c_int, C.c_int,
-                 C.c_uint64, C.c_uint32, C.c_uint64, _i32p)
+                 C.c_uint64, C.c_uint32, C.c_uint64, C.c_int, _i32p)
 _code_value = _sig("gqo_code_value", C.c_int64, C.c_int, C.c_int32)
 _aggregate = _sig("gqo_aggregate", None, C.POINTER(_i32p), C.c_int, C.c_int64, C.c_int, _i64p)
 _max_aggregate = _sig("gqo_max_aggregate", C.c_int64, C.c_int, C.c_int, C.c_int)
@@ -51,7 +51,7 @@ _signplane_words = _sig("gqo_signplane_words", C.c_int64, C.c_int64)
 _pack = _sig("gqo_pack", C.c_int, _i32p, C.c_int64, C.c_int, _u8p, _u32p)
 _unpack = _sig("gqo_unpack", None, _u8p, _u32p, C.c_int64, C.c_int, _i32p)
 _quantize_aggregate = _sig("gqo_quantize_aggregate", C.c_int, C.POINTER(_f32p), C.c_int, C.c_int64,
-                           C.c_float, C.c_int, C.c_int, C.c_uint64, C.c_uint64, _i64p)
+                           C.c_float, C.c_int, C.c_int, C.c_uint64, C.c_uint64, C.c_int, _i64p)
 
 
 _alg2_k = _sig("gqo_alg2_k", C.c_int, C.c_uint32)
@@ -100,10 +100,11 @@ def philox4x32(ctr, key, rounds=10):
     return o
 
 
-def random_words(seed, worker, index_base, d):
-    """The 32 random bits of each coordinate index_base .. index_base+d-1 of one worker."""
+def random_words(seed, worker, index_base, d, rng_bits=32):
+    """The word that rounds each coordinate index_base .. index_base+d-1 of one worker: 32 random bits, or
+    with rng_bits = 16 the coordinate's 16 random bits in the top half and zeros below."""
     r = np.zeros(int(d), np.uint32)
-    _random_words(int(seed), int(worker), int(index_base), int(d), _ptr(r, C.c_uint32))
+    _random_words(int(seed), int(worker), int(index_base), int(d), int(rng_bits), _ptr(r, C.c_uint32))
     return r
 
 
@@ -131,12 +132,12 @@ def quantize_with_words(x, r, norm, scheme, s):
     return q
 
 
-def quantize(x, norm, scheme, s, seed, worker, index_base=0):
+def quantize(x, norm, scheme, s, seed, worker, index_base=0, rng_bits=32):
     """Algorithm 1 lines 2-5 for one worker: signed level integers, one int32 per coordinate."""
     x = _arr(x, np.float32).reshape(-1)
     q = np.zeros(x.shape[0], np.int32)
     _quantize(_ptr(x, C.c_float), x.shape[0], float(np.float32(norm)), int(scheme), int(s),
-              int(seed), int(worker), int(index_base), _ptr(q, C.c_int32))
+              int(seed), int(worker), int(index_base), int(rng_bits), _ptr(q, C.c_int32))
     return q
 
 
@@ -195,12 +196,12 @@ def unpack(levels, signplane, d, fmt):
     return q
 
 
-def quantize_aggregate(xs, norm, scheme, s, seed, index_base=0):
+def quantize_aggregate(xs, norm, scheme, s, seed, index_base=0, rng_bits=32):
     """Quantize every worker (worker word = position in xs) and sum: the unfused composition."""
     rows, ptrs, K, d = _rows(xs, np.float32, C.c_float)
     A = np.zeros(d, np.int64)
     rc = _quantize_aggregate(ptrs, K, d, float(np.float32(norm)), int(scheme), int(s), int(seed),
-                             int(index_base), _ptr(A, C.c_int64))
+                             int(index_base), int(rng_bits), _ptr(A, C.c_int64))
     if rc != 0:
         raise MemoryError("oracle could not allocate the code vectors")
     return A
