@@ -114,6 +114,15 @@ def time_rows(gq, torch, xs, norm, params, cfg, args):
     rows["fused_dequant"] = timed(lambda: gq.fused_quantize_aggregate(xs, norm, p, 0, None, out), d * (4.0 * K + 4.0))
     rows["fused_agg_levels"] = timed(lambda: gq.fused_quantize_aggregate(xs, norm, p, 0, agg, None, lvs, sps),
                                      d * (4.0 * K + K * lvb + abytes))
+    # short draws: 16 random bits per coordinate, one Philox call per eight coordinates
+    p16 = gq.make_params(params.scheme, params.s, pack, aggf, seed=params.seed, rng_bits=16)
+
+    def quantize_all_16():
+        for i in range(K):
+            gq.quantize(xs[i], norm, p16, i, 0, lvs[i], sps[i] if plane else None)
+
+    rows["fused_agg_rng16"] = timed(lambda: gq.fused_quantize_aggregate(xs, norm, p16, 0, agg, None), d * (4.0 * K + abytes))
+    rows["quantize_xK_rng16"] = timed(quantize_all_16, K * d * (4.0 + lvb))
     if params.scheme == gq.GQ_EXP:
         # Algorithm 2 on int8 codes: reduced (sign, e) bytes and the fp32 mean; ALU-bound (K-1 Philox calls and
         # branch-free pair reductions per four coordinates), so GB/s here is far below the HBM roof by design

@@ -20,7 +20,7 @@
  *              failure is returned as GQ_ERR_DEVICE.  Conditions that depend on the data are
  *              reported through the device word `status_flags` of gq_global_norm.
  *   sizes      1 <= K <= GQ_MAX_WORKERS, d >= 0 (d = 0 is a valid no-op), any d (ragged tails are
- *              handled inside), index_base >= 0 and a multiple of 4.
+ *              handled inside), index_base >= 0 and a multiple of 4 (of 8 with rng_bits = 16).
  *
  * The stored integer ("code").  The paper numbers levels downwards, l_0 = 1 > ... > l_s = 0
  * (Definition 1).  The integer stored and summed is k = s - u for level l_u, signed with sign(x):
@@ -35,6 +35,12 @@
  *   exponential  z = min(fl32(|x| * fl32(2^(s-1)/norm)), 2^(s-1));  R = r >> 9;
  *                z >= 1: round the binary32 z up to the next power of two iff mantissa + R >= 2^23;
  *                z <  1: k = 1 iff rne(z * 2^23) + R >= 2^23, else 0
+ * Short draws (rng_bits = 16): one Philox call serves the eight coordinates 8c .. 8c+7, counter
+ * (lo32(g/8), hi32(g/8), worker, 0); coordinate g takes the low (g even) or high (g odd) half of word
+ * (g mod 8) / 2 as the TOP half of r, zeros below, and the two rules apply unchanged: the probability
+ * of Eq. (2) is then met to 2^-16 and the generator costs half as much per coordinate.  index_base
+ * must then be a multiple of 8.  Only gq_quantize and gq_fused_quantize_aggregate draw from this
+ * stream; the other calls ignore rng_bits.
  * A norm that is zero or not finite (or so small that the scale overflows) gives all-zero codes.
  * Inputs must be finite with |x| <= norm; otherwise codes stay within [-s, s] but are unspecified.
  */
@@ -85,6 +91,8 @@ typedef struct {
     int32_t s;        /* number of non-zero levels, s >= 1 (exponential: s <= 31)          */
     int32_t pack;     /* gq_pack: format of level buffers (ignored where none is touched) */
     int32_t agg;      /* gq_agg: format of the integer sum (ignored where none is touched) */
+    int32_t rng_bits; /* random bits per coordinate of the quantisation draw: 32 (0 reads as 32) or 16 */
+    int32_t reserved; /* set to 0                                                         */
     uint64_t seed;    /* Philox key                                                       */
 } gq_params;
 

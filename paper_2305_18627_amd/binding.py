@@ -27,7 +27,7 @@ EXPORTS = ("gq_version", "gq_status_string", "gq_check_width", "gq_norm_workspac
 
 class gq_params(C.Structure):
     _fields_ = [("scheme", C.c_int32), ("s", C.c_int32), ("pack", C.c_int32), ("agg", C.c_int32),
-                ("seed", C.c_uint64)]
+                ("rng_bits", C.c_int32), ("reserved", C.c_int32), ("seed", C.c_uint64)]
 
 
 class GQError(RuntimeError):
@@ -99,8 +99,8 @@ def _check(st, where):
         raise GQError(st, where)
 
 
-def make_params(scheme, s, pack=GQ_PACK_I8, agg=GQ_AGG_I32, seed=0):
-    return gq_params(int(scheme), int(s), int(pack), int(agg), int(seed))
+def make_params(scheme, s, pack=GQ_PACK_I8, agg=GQ_AGG_I32, seed=0, rng_bits=32):
+    return gq_params(int(scheme), int(s), int(pack), int(agg), int(rng_bits), 0, int(seed))
 
 
 def levels_nbytes(d, pack):

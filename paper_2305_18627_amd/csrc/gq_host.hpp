@@ -24,8 +24,12 @@ static inline gq_status check_params(const gq_params *p, bool uses_pack, bool us
         if (p->s > lim) return GQ_ERR_UNSUPPORTED;
     }
     if (uses_agg && p->agg != GQ_AGG_I32 && p->agg != GQ_AGG_I16) return GQ_ERR_INVALID_ARG;
+    if (p->rng_bits != 0 && p->rng_bits != 16 && p->rng_bits != 32) return GQ_ERR_INVALID_ARG;
     return GQ_OK;
 }
+
+// 16 random bits per coordinate instead of 32 (one Philox call per eight coordinates)
+static inline bool short_draws(const gq_params *p) { return p->rng_bits == 16; }
 
 static inline int64_t max_aggregate(const gq_params *p, int K)
 {

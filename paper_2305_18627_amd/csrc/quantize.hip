@@ -2,9 +2,11 @@
 // to integer codes, for one worker with the codes stored, or for all K workers with the integer sum
 // formed in registers.  The contract of the entry points is stated in include/gqsgd.h.
 //
-// Data layout.  Every buffer is a flat array in HBM.  A lane always owns four consecutive
-// coordinates of a gradient (one 128-bit load per worker), which are also the four words of one
-// Philox call, so that a wave reads 1 KiB of contiguous gradient per worker and load.  All traffic is
+// Data layout.  Every buffer is a flat array in HBM.  A lane owns vectors of four consecutive
+// coordinates of a gradient (one 128-bit load per worker and vector), so that a wave reads 1 KiB of
+// contiguous gradient per load.  With full draws (32 random bits per coordinate) a lane owns one
+// vector, whose coordinates take the four words of one Philox call; with short draws (16 bits) it owns
+// two vectors 64 apart and shares the words of its call with its neighbour lane.  All traffic is
 // streaming with no reuse: nothing is staged through LDS.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -25,6 +27,7 @@ namespace gq {
 //   UNIFORM_HI  the high word of the Philox call index is the same for the whole launch
 //   WINDOWS     keep few loads in flight per lane and store the sum only inside chip-wide time
 //               windows (see below)
+//   HALF        short draws: 16 random bits per coordinate, one Philox call per eight coordinates
 // =============================================================================================
 __device__ __forceinline__ f32x4 load_coords(const float *x, int64_t v, int nvalid)
 {
@@ -46,21 +49,24 @@ __device__ __forceinline__ uint32_t or_over_8_lanes(uint32_t v)
     return v;
 }
 
-__device__ __forceinline__ void store_codes(void *lv, uint32_t *sp, int pack, int64_t v, int nvalid, int64_t d,
-                                            int q0, int q1, int q2, int q3)
+// Store the codes q[0..3] of vector v (nvalid of its coordinates exist).  The lanes of a wave must hold
+// consecutive vectors, lane 0 a multiple of 8, and all be active (the sign words are assembled across lanes).
+__device__ __forceinline__ void store_codes(void *lv, uint32_t *sp, int pack, int64_t v, int nvalid, int64_t d, int *q)
 {
-    const bool plane = pack >= 2;
-    if (plane) {
-        const uint32_t nib = (uint32_t)(q0 < 0) | ((uint32_t)(q1 < 0) << 1) | ((uint32_t)(q2 < 0) << 2) |
-                             ((uint32_t)(q3 < 0) << 3);
+    if (pack >= 2) {
+        uint32_t nib = 0;
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            nib |= (uint32_t)(q[i] < 0) << i;
+            q[i] = abs(q[i]);
+        }
         const uint32_t word = or_over_8_lanes(nib << (4 * (threadIdx.x & 7)));
         if ((threadIdx.x & 7) == 0 && ((v & ~(int64_t)7) << 2) < d) sp[v >> 3] = word;
-        q0 = abs(q0); q1 = abs(q1); q2 = abs(q2); q3 = abs(q3);
     }
     if (nvalid == 0) return;
     if (pack == GQ_PACK_I8 || pack == GQ_PACK_U8_SIGNPLANE) {
-        const uint32_t w = (uint32_t)(q0 & 255) | ((uint32_t)(q1 & 255) << 8) | ((uint32_t)(q2 & 255) << 16) |
-                           ((uint32_t)(q3 & 255) << 24);
+        const uint32_t w = (uint32_t)(q[0] & 255) | ((uint32_t)(q[1] & 255) << 8) | ((uint32_t)(q[2] & 255) << 16) |
+                           ((uint32_t)(q[3] & 255) << 24);
         if (nvalid == 4) {
             __builtin_nontemporal_store(w, reinterpret_cast<uint32_t *>(lv) + v);
         } else {
@@ -68,8 +74,8 @@ __device__ __forceinline__ void store_codes(void *lv, uint32_t *sp, int pack, in
             for (int i = 0; i < nvalid; i++) b[i] = (uint8_t)(w >> (8 * i));
         }
     } else {
-        const uint32_t w = (uint32_t)(q0 & 15) | ((uint32_t)(q1 & 15) << 4) | ((uint32_t)(q2 & 15) << 8) |
-                           ((uint32_t)(q3 & 15) << 12);
+        const uint32_t w = (uint32_t)(q[0] & 15) | ((uint32_t)(q[1] & 15) << 4) | ((uint32_t)(q[2] & 15) << 8) |
+                           ((uint32_t)(q[3] & 15) << 12);
         if (nvalid == 4) {
             __builtin_nontemporal_store((uint16_t)w, reinterpret_cast<uint16_t *>(lv) + v);
         } else {
@@ -116,78 +122,147 @@ constexpr uint32_t kWindowTicksPerWorker = 62;    // ticks of the 100 MHz counte
 constexpr int kWindowMinWorkers = 8;
 constexpr double kWindowMinLoads = 2.5e8;         // K * d from which the windows win (measured)
 
-// The launch covers the 4-coordinate vectors v0 <= v < vend of the buffers.  With UNIFORM_HI the
-// host guarantees that the Philox call index (call_base + v) does not cross a multiple of 2^32 inside
-// the launch, so the high counter word is a scalar: the first round and half of the second are then
-// shared by all lanes or all workers and leave the vector ALU.
-template <int SCHEME, int KT, bool LEVELS, bool UNIFORM_HI, bool WINDOWS>
+// Short draws (16 random bits per coordinate): one Philox call serves the eight coordinates of two
+// neighbouring vectors 2c and 2c+1.  To keep every load and store of a wave contiguous, a wave takes 128
+// consecutive vectors and lane l owns vectors l ("A") and 64 + l ("B") of them.  Even lane 2i runs the call
+// of vectors 2i, 2i+1 of the A half, odd lane 2i+1 the call of vectors 2i, 2i+1 of the B half, and the two
+// lanes swap the half of the words the other needs (one DPP exchange of two registers).  Afterwards
+// word pair `a` rounds the lane's A vector and `b` its B vector; coordinate j of a vector takes the low
+// (j even) or high (j odd) half of word j / 2 of its pair, moved to the top of a 32-bit word with zeros
+// below, so that the rounding rules apply unchanged.  Every lane of the wave must be active.
+struct ShortDraws { uint32_t a[2], b[2]; };
+__device__ __forceinline__ ShortDraws share_short_draws(const Words4 &r, bool odd)
+{
+    const uint32_t got0 = dpp32<kDppQuadXor1>(odd ? r.w[0] : r.w[2]);
+    const uint32_t got1 = dpp32<kDppQuadXor1>(odd ? r.w[1] : r.w[3]);
+    ShortDraws o;
+    o.a[0] = odd ? got0 : r.w[0]; o.a[1] = odd ? got1 : r.w[1];
+    o.b[0] = odd ? r.w[2] : got0; o.b[1] = odd ? r.w[3] : got1;
+    return o;
+}
+__device__ __forceinline__ uint32_t short_draw(const uint32_t *pair, int j)
+{
+    return (j & 1) ? (pair[j >> 1] & 0xFFFF0000u) : (pair[j >> 1] << 16);
+}
+
+// The launch covers the vectors v0 <= v < vend of the buffers (HALF: v0 = 0).  With UNIFORM_HI the host
+// guarantees that the Philox call index does not cross a multiple of 2^32 inside the launch, so the high
+// counter word is a scalar: the first round and half of the second are then shared by all lanes or all
+// workers and leave the vector ALU.
+template <int SCHEME, int KT, bool LEVELS, bool UNIFORM_HI, bool WINDOWS, bool HALF>
 __global__ void __launch_bounds__(kFusedBlock)
 quantize_aggregate_kernel(GradPtrs P, LevelPtrs L, int K, int64_t d, int64_t v0, int64_t vend, const float *__restrict__ norm, int s,
                           uint64_t seed, uint32_t worker0, uint64_t call_base, int pack,
                           void *__restrict__ agg_out, int agg_fmt, float *__restrict__ deq_out, float deq_div,
                           uint32_t win_period, uint32_t win_open)
 {
-    const int64_t v = v0 + (int64_t)blockIdx.x * kFusedBlock + threadIdx.x;
+    constexpr int NV = HALF ? 2 : 1;             // vectors per lane
     const int64_t nfull = d >> 2;
-    const int nvalid = v >= vend ? 0 : (v < nfull ? 4 : (v == nfull ? (int)(d & 3) : 0));
-    if (!LEVELS && nvalid == 0) return;          // with LEVELS the sign-plane exchange needs whole waves
+    const int lane = (int)(threadIdx.x & 63u);
+    int64_t v[NV];
+    uint32_t local_call;                         // call index of this lane relative to the launch's first
+    if (HALF) {
+        const uint32_t chunk = blockIdx.x * (kFusedBlock / 64) + (threadIdx.x >> 6);   // 128 vectors per wave
+        v[0] = v0 + (int64_t)chunk * 128 + lane;
+        v[NV - 1] = v[0] + 64;
+        local_call = chunk * 64u + (uint32_t)(lane >> 1) + (uint32_t)(lane & 1) * 32u;
+    } else {
+        local_call = blockIdx.x * kFusedBlock + threadIdx.x;
+        v[0] = v0 + (int64_t)local_call;
+    }
+    int nvalid[NV];
+#pragma unroll
+    for (int t = 0; t < NV; t++) nvalid[t] = v[t] >= vend ? 0 : (v[t] < nfull ? 4 : (v[t] == nfull ? (int)(d & 3) : 0));
+    // whole waves are needed by the sign-plane exchange (LEVELS) and by the exchange of short draws
+    if (!LEVELS && !HALF && nvalid[0] == 0) return;
 
     const float nrm = *norm;
     const Scale sc = make_scale<SCHEME>(nrm, s);
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    const uint64_t first = call_base + (uint64_t)(HALF ? (v0 >> 1) : v0);      // scalar
     uint32_t c_lo, c_hi;
     if (UNIFORM_HI) {
-        const uint64_t first = call_base + (uint64_t)v0;                      // scalar
         c_hi = (uint32_t)(first >> 32);
-        c_lo = (uint32_t)first + (uint32_t)(blockIdx.x * kFusedBlock + threadIdx.x);   // no carry (host)
+        c_lo = (uint32_t)first + local_call;                                      // no carry (host)
     } else {
-        const uint64_t call = call_base + (uint64_t)v;
+        const uint64_t call = first + (uint64_t)local_call;
         c_lo = (uint32_t)call;
         c_hi = (uint32_t)(call >> 32);
     }
     const int Kc = KT > 0 ? KT : K;
+    const bool whole = nvalid[NV - 1] == 4;      // every coordinate of the lane exists
 
-    Acc<SCHEME> acc;
-    auto one_worker = [&](int w, const f32x4 &g) {
+    struct Unit { f32x4 g[NV]; };
+    auto fetch = [&](int w) {
+        Unit x;
+#pragma unroll
+        for (int t = 0; t < NV; t++) x.g[t] = load_coords(P.x[w], v[t], nvalid[t]);
+        return x;
+    };
+    auto fetch_whole = [&](int w) {
+        Unit x;
+#pragma unroll
+        for (int t = 0; t < NV; t++) x.g[t] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(P.x[w]) + v[t]);
+        return x;
+    };
+    Acc<SCHEME> acc[NV];
+    auto one_worker = [&](int w, const Unit &x) {
         const Words4 r = philox4x32_10(c_lo, c_hi, worker0 + (uint32_t)w, 0u, k0, k1);
-        const float f0 = Round<SCHEME>::value(g.x, sc, r.w[0]);
-        const float f1 = Round<SCHEME>::value(g.y, sc, r.w[1]);
-        const float f2 = Round<SCHEME>::value(g.z, sc, r.w[2]);
-        const float f3 = Round<SCHEME>::value(g.w, sc, r.w[3]);
-        acc.add(f0, f1, f2, f3);
-        if (LEVELS) {
-            store_codes(L.lv[w], L.sp[w], pack, v, nvalid, d, Round<SCHEME>::code_of_value(f0),
-                        Round<SCHEME>::code_of_value(f1), Round<SCHEME>::code_of_value(f2),
-                        Round<SCHEME>::code_of_value(f3));
+        uint32_t draw[NV][4];
+        if (HALF) {
+            const ShortDraws sd = share_short_draws(r, (lane & 1) != 0);
+#pragma unroll
+            for (int j = 0; j < 4; j++) { draw[0][j] = short_draw(sd.a, j); draw[NV - 1][j] = short_draw(sd.b, j); }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; j++) draw[0][j] = r.w[j];
+        }
+#pragma unroll
+        for (int t = 0; t < NV; t++) {
+            const float f0 = Round<SCHEME>::value(x.g[t].x, sc, draw[t][0]);
+            const float f1 = Round<SCHEME>::value(x.g[t].y, sc, draw[t][1]);
+            const float f2 = Round<SCHEME>::value(x.g[t].z, sc, draw[t][2]);
+            const float f3 = Round<SCHEME>::value(x.g[t].w, sc, draw[t][3]);
+            acc[t].add(f0, f1, f2, f3);
+            if (LEVELS) {
+                int q[4] = {Round<SCHEME>::code_of_value(f0), Round<SCHEME>::code_of_value(f1),
+                            Round<SCHEME>::code_of_value(f2), Round<SCHEME>::code_of_value(f3)};
+                store_codes(L.lv[w], L.sp[w], pack, v[t], nvalid[t], d, q);
+            }
         }
     };
     if (KT > 0) {
-        constexpr int kInFlight = WINDOWS ? (KT > 4 ? 4 : (KT > 0 ? KT : 1)) : (KT > 16 ? 16 : (KT > 0 ? KT : 1));   // loads issued before the first is consumed
+        // workers whose loads are issued before the first is consumed: few with WINDOWS, else up to 16
+        // vectors; the bound is enforced (accumulators pinned) where the hoisted loads would not fit
+        constexpr int kMost = WINDOWS ? 4 : 16 / NV;
+        constexpr bool kPin = WINDOWS || HALF;
+        constexpr int kInFlight = KT > kMost ? kMost : (KT > 0 ? KT : 1);
 #pragma unroll
         for (int w0 = 0; w0 < KT; w0 += kInFlight) {
-            f32x4 g[kInFlight];
-            if (nvalid == 4) {                       // one branch per batch, not per worker
+            Unit x[kInFlight];
+            if (whole) {                             // one branch per batch, not per worker
 #pragma unroll
-                for (int j = 0; j < kInFlight; j++)
-                    g[j] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(P.x[w0 + j]) + v);
+                for (int j = 0; j < kInFlight; j++) x[j] = fetch_whole(w0 + j);
             } else {
 #pragma unroll
-                for (int j = 0; j < kInFlight; j++) g[j] = load_coords(P.x[w0 + j], v, nvalid);
+                for (int j = 0; j < kInFlight; j++) x[j] = fetch(w0 + j);
             }
 #pragma unroll
-            for (int j = 0; j < kInFlight; j++) one_worker(w0 + j, g[j]);
-            if (WINDOWS) acc.pin();
+            for (int j = 0; j < kInFlight; j++) one_worker(w0 + j, x[j]);
+            if (kPin) {
+#pragma unroll
+                for (int t = 0; t < NV; t++) acc[t].pin();
+            }
         }
     } else {
         int w = 0;
         for (; w + 4 <= Kc; w += 4) {
-            const f32x4 g0 = load_coords(P.x[w], v, nvalid), g1 = load_coords(P.x[w + 1], v, nvalid);
-            const f32x4 g2 = load_coords(P.x[w + 2], v, nvalid), g3 = load_coords(P.x[w + 3], v, nvalid);
-            one_worker(w, g0); one_worker(w + 1, g1); one_worker(w + 2, g2); one_worker(w + 3, g3);
+            const Unit x0 = fetch(w), x1 = fetch(w + 1), x2 = fetch(w + 2), x3 = fetch(w + 3);
+            one_worker(w, x0); one_worker(w + 1, x1); one_worker(w + 2, x2); one_worker(w + 3, x3);
         }
-        for (; w < Kc; w++) one_worker(w, load_coords(P.x[w], v, nvalid));
+        for (; w < Kc; w++) one_worker(w, fetch(w));
     }
-    if (nvalid == 0) return;
+    if (nvalid[0] == 0) return;
 
     if (WINDOWS) {
         for (int it = 0; it < 4096; it++) {
@@ -196,115 +271,173 @@ quantize_aggregate_kernel(GradPtrs P, LevelPtrs L, int K, int64_t d, int64_t v0,
             __builtin_amdgcn_s_sleep(8);
         }
     }
-    const i32x4 a = acc.get();
-    if (agg_out) {
-        if (agg_fmt == GQ_AGG_I32) {
-            if (nvalid == 4) {
-                __builtin_nontemporal_store(a, reinterpret_cast<i32x4 *>(agg_out) + v);
+    const float c = sc.scale != 0.0f ? nrm / deq_div : 0.0f;         // Eq. (1): norm / (n * unit)
+#pragma unroll
+    for (int t = 0; t < NV; t++) {
+        const int nv = nvalid[t];
+        if (nv == 0) break;
+        const i32x4 a = acc[t].get();
+        if (agg_out) {
+            if (agg_fmt == GQ_AGG_I32) {
+                if (nv == 4) {
+                    __builtin_nontemporal_store(a, reinterpret_cast<i32x4 *>(agg_out) + v[t]);
+                } else {
+                    int *o = reinterpret_cast<int *>(agg_out) + (v[t] << 2);
+                    o[0] = a.x;
+                    if (nv > 1) o[1] = a.y;
+                    if (nv > 2) o[2] = a.z;
+                }
             } else {
-                int *o = reinterpret_cast<int *>(agg_out) + (v << 2);
-                o[0] = a.x;
-                if (nvalid > 1) o[1] = a.y;
-                if (nvalid > 2) o[2] = a.z;
-            }
-        } else {
-            if (nvalid == 4) {
-                const i16x4 o = {(short)a.x, (short)a.y, (short)a.z, (short)a.w};
-                __builtin_nontemporal_store(o, reinterpret_cast<i16x4 *>(agg_out) + v);
-            } else {
-                short *o = reinterpret_cast<short *>(agg_out) + (v << 2);
-                o[0] = (short)a.x;
-                if (nvalid > 1) o[1] = (short)a.y;
-                if (nvalid > 2) o[2] = (short)a.z;
+                if (nv == 4) {
+                    const i16x4 o = {(short)a.x, (short)a.y, (short)a.z, (short)a.w};
+                    __builtin_nontemporal_store(o, reinterpret_cast<i16x4 *>(agg_out) + v[t]);
+                } else {
+                    short *o = reinterpret_cast<short *>(agg_out) + (v[t] << 2);
+                    o[0] = (short)a.x;
+                    if (nv > 1) o[1] = (short)a.y;
+                    if (nv > 2) o[2] = (short)a.z;
+                }
             }
         }
-    }
-    if (deq_out) {
-        const float c = sc.scale != 0.0f ? nrm / deq_div : 0.0f;     // Eq. (1): norm / (n * unit)
-        if (nvalid == 4) {
-            const f32x4 o = {(float)a.x * c, (float)a.y * c, (float)a.z * c, (float)a.w * c};
-            __builtin_nontemporal_store(o, reinterpret_cast<f32x4 *>(deq_out) + v);
-        } else {
-            float *o = deq_out + (v << 2);
-            o[0] = (float)a.x * c;
-            if (nvalid > 1) o[1] = (float)a.y * c;
-            if (nvalid > 2) o[2] = (float)a.z * c;
+        if (deq_out) {
+            if (nv == 4) {
+                const f32x4 o = {(float)a.x * c, (float)a.y * c, (float)a.z * c, (float)a.w * c};
+                __builtin_nontemporal_store(o, reinterpret_cast<f32x4 *>(deq_out) + v[t]);
+            } else {
+                float *o = deq_out + (v[t] << 2);
+                o[0] = (float)a.x * c;
+                if (nv > 1) o[1] = (float)a.y * c;
+                if (nv > 2) o[2] = (float)a.z * c;
+            }
         }
     }
 }
 
 // =============================================================================================
 // Algorithm 1 lines 2-5 for one worker with the codes stored: a lane owns kQuantVec vectors of four
-// coordinates, kQuantBlock vectors apart, and issues all its loads before the first Philox call.
+// coordinates, kQuantBlock vectors apart (short draws: two pairs 64 apart, see share_short_draws), and
+// issues all its loads before the first Philox call.
 // =============================================================================================
 constexpr int kQuantBlock = 128;
 constexpr int kQuantVec = 4;
 
-template <int SCHEME, bool UNIFORM_HI>
+template <int SCHEME, bool UNIFORM_HI, bool HALF>
 __global__ void __launch_bounds__(kQuantBlock)
 quantize_kernel(const float *__restrict__ x, void *__restrict__ lv, uint32_t *__restrict__ sp, int64_t d,
                 const float *__restrict__ norm, int s, uint64_t seed, uint32_t worker, uint64_t call_base, int pack)
 {
     const int64_t nfull = d >> 2;
-    const int64_t base = (int64_t)blockIdx.x * (kQuantBlock * kQuantVec) + threadIdx.x;
+    const int lane = (int)(threadIdx.x & 63u);
     const Scale sc = make_scale<SCHEME>(*norm, s);
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    // vector j of this lane and the Philox call that it runs for vectors j, j+1 (short draws) or j (full)
+    int64_t v[kQuantVec];
+    int64_t call[kQuantVec];
+#pragma unroll
+    for (int j = 0; j < kQuantVec; j++) {
+        if (HALF) {
+            // the workgroup's 512 vectors are four chunks of 128; wave w takes chunks w and w + 2
+            const int64_t chunk = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6) + 2 * (j >> 1);
+            v[j] = chunk * 128 + 64 * (j & 1) + lane;
+            call[j] = chunk * 64 + (lane >> 1) + (lane & 1) * 32;
+        } else {
+            v[j] = (int64_t)blockIdx.x * (kQuantBlock * kQuantVec) + (int64_t)j * kQuantBlock + threadIdx.x;
+            call[j] = v[j];
+        }
+    }
     f32x4 g[kQuantVec];
     int nvalid[kQuantVec];
 #pragma unroll
     for (int j = 0; j < kQuantVec; j++) {
-        const int64_t v = base + (int64_t)j * kQuantBlock;
-        nvalid[j] = v < nfull ? 4 : (v == nfull ? (int)(d & 3) : 0);
-        g[j] = load_coords(x, v, nvalid[j]);
+        nvalid[j] = v[j] < nfull ? 4 : (v[j] == nfull ? (int)(d & 3) : 0);
+        g[j] = load_coords(x, v[j], nvalid[j]);
     }
-#pragma unroll
-    for (int j = 0; j < kQuantVec; j++) {            // no lane leaves early: the sign-plane exchange needs whole waves
-        const int64_t v = base + (int64_t)j * kQuantBlock;
-        uint32_t c_lo, c_hi;
-        if (UNIFORM_HI) {                             // host: call_base + v stays below the next multiple of 2^32
+    auto counter = [&](int64_t c, uint32_t &c_lo, uint32_t &c_hi) {
+        if (UNIFORM_HI) {                             // host: call_base + c stays below the next multiple of 2^32
             c_hi = (uint32_t)(call_base >> 32);
-            c_lo = (uint32_t)call_base + (uint32_t)v;
+            c_lo = (uint32_t)call_base + (uint32_t)c;
         } else {
-            const uint64_t call = call_base + (uint64_t)v;
-            c_lo = (uint32_t)call;
-            c_hi = (uint32_t)(call >> 32);
+            const uint64_t cc = call_base + (uint64_t)c;
+            c_lo = (uint32_t)cc;
+            c_hi = (uint32_t)(cc >> 32);
         }
-        const Words4 r = philox4x32_10(c_lo, c_hi, worker, 0u, k0, k1);
-        store_codes(lv, sp, pack, v, nvalid[j], d,
-                    Round<SCHEME>::code_of_value(Round<SCHEME>::value(g[j].x, sc, r.w[0])),
-                    Round<SCHEME>::code_of_value(Round<SCHEME>::value(g[j].y, sc, r.w[1])),
-                    Round<SCHEME>::code_of_value(Round<SCHEME>::value(g[j].z, sc, r.w[2])),
-                    Round<SCHEME>::code_of_value(Round<SCHEME>::value(g[j].w, sc, r.w[3])));
+    };
+    auto emit = [&](int j, const uint32_t *draw) {
+        int q[4] = {Round<SCHEME>::code_of_value(Round<SCHEME>::value(g[j].x, sc, draw[0])),
+                    Round<SCHEME>::code_of_value(Round<SCHEME>::value(g[j].y, sc, draw[1])),
+                    Round<SCHEME>::code_of_value(Round<SCHEME>::value(g[j].z, sc, draw[2])),
+                    Round<SCHEME>::code_of_value(Round<SCHEME>::value(g[j].w, sc, draw[3]))};
+        store_codes(lv, sp, pack, v[j], nvalid[j], d, q);
+    };
+    // no lane leaves early: the sign-plane exchange and the exchange of short draws need whole waves
+    if (HALF) {
+#pragma unroll
+        for (int j = 0; j < kQuantVec; j += 2) {
+            uint32_t c_lo, c_hi;
+            counter(call[j], c_lo, c_hi);
+            const ShortDraws sd = share_short_draws(philox4x32_10(c_lo, c_hi, worker, 0u, k0, k1), (lane & 1) != 0);
+            uint32_t da[4], db[4];
+#pragma unroll
+            for (int i = 0; i < 4; i++) { da[i] = short_draw(sd.a, i); db[i] = short_draw(sd.b, i); }
+            emit(j, da);
+            emit(j + 1, db);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < kQuantVec; j++) {
+            uint32_t c_lo, c_hi;
+            counter(call[j], c_lo, c_hi);
+            const Words4 r = philox4x32_10(c_lo, c_hi, worker, 0u, k0, k1);
+            emit(j, r.w);
+        }
     }
 }
 
-template <int SCHEME>
+template <int SCHEME, bool HALF>
 static gq_status launch_quantize_aggregate(const GradPtrs &P, const LevelPtrs &L, bool levels, int K, int64_t d,
                                            const float *norm, const gq_params *p, uint32_t worker0,
                                            int64_t index_base, void *agg_out, float *deq_out, hipStream_t st)
 {
+    constexpr int kLaneVecs = HALF ? 2 : 1;              // vectors per lane = vectors per Philox call
     const int64_t nvec = (d + 3) / 4;
-    const uint64_t call_base = (uint64_t)index_base / 4u;
+    const uint64_t call_base = (uint64_t)index_base / (uint64_t)(4 * kLaneVecs);
     const float div = dequant_divisor(p, K);
     const dim3 block(kFusedBlock);
     // Write windows pay once a launch lasts many periods and a wave's K loads span about one period;
     // below these sizes the wait for the next window costs more than the cleaner read/write mix gains.
     const bool win = !levels && K >= kWindowMinWorkers && (double)K * (double)d >= kWindowMinLoads;
-    const uint32_t win_period = kWindowTicksPerWorker * (uint32_t)K;
+    const uint32_t win_period = kWindowTicksPerWorker * (uint32_t)K * (uint32_t)kLaneVecs;   // a wave loads kLaneVecs KiB per worker
     const uint32_t win_open = win_period / 10u;
-#define GQ_LAUNCH(KT, LV, UH, WIN, V0, COUNT)                                                                      \
+#define GQ_LAUNCH(KT, LV, UH, WIN, V0, COUNT)                                                                  \
     do {                                                                                                      \
-        const int64_t blocks_ = ((COUNT) + kFusedBlock - 1) / kFusedBlock;                                    \
+        const int64_t blocks_ = ((COUNT) + kFusedBlock * kLaneVecs - 1) / (kFusedBlock * kLaneVecs);          \
         if (!grid_fits(blocks_)) return GQ_ERR_INVALID_ARG;                                                   \
-        hipLaunchKernelGGL((quantize_aggregate_kernel<SCHEME, KT, LV, UH, WIN>), dim3((unsigned)blocks_), block, 0, st, \
-                           P, L, K, d, (int64_t)(V0), (int64_t)(V0) + (int64_t)(COUNT), norm, p->s, p->seed, worker0, call_base, p->pack,       \
-                           agg_out, p->agg, deq_out, div, win_period, win_open);                                                    \
+        hipLaunchKernelGGL((quantize_aggregate_kernel<SCHEME, KT, LV, UH, WIN, HALF>), dim3((unsigned)blocks_), block, 0, st, \
+                           P, L, K, d, (int64_t)(V0), (int64_t)(V0) + (int64_t)(COUNT), norm, p->s, p->seed, worker0,  \
+                           call_base, p->pack, agg_out, p->agg, deq_out, div, win_period, win_open);          \
     } while (0)
+#define GQ_LAUNCH_K(UH, WIN, V0, COUNT)                                                                        \
+    do {                                                                                                      \
+        if (K == 4) GQ_LAUNCH(4, false, UH, WIN, V0, COUNT);                                                  \
+        else if (K == 8) GQ_LAUNCH(8, false, UH, WIN, V0, COUNT);                                             \
+        else if (K == 16) GQ_LAUNCH(16, false, UH, WIN, V0, COUNT);                                           \
+        else if (K == 32) GQ_LAUNCH(32, false, UH, WIN, V0, COUNT);                                           \
+        else GQ_LAUNCH(0, false, UH, WIN, V0, COUNT);                                                         \
+    } while (0)
+    // calls of the launch, counting the lanes past the end of whole workgroups
+    const uint64_t calls_padded = (uint64_t)((nvec + kFusedBlock * kLaneVecs - 1) / (kFusedBlock * kLaneVecs)) * kFusedBlock;
+    const bool one_stretch = ((call_base & 0xFFFFFFFFull) + calls_padded) <= ((uint64_t)1 << 32);
     if (levels) {
-        // storing codes: one launch; the scalar high word is used when the bucket does not cross 2^34
-        const bool one_stretch = ((call_base & 0xFFFFFFFFull) + (uint64_t)nvec) <= ((uint64_t)1 << 32);
+        // storing codes: one launch; the scalar high word is used when the bucket does not cross 2^32 calls
         if (one_stretch) GQ_LAUNCH(0, true, true, false, 0, nvec);
         else GQ_LAUNCH(0, true, false, false, 0, nvec);
+        return launched();
+    }
+    if (HALF) {
+        // short draws pair the lanes of a wave, so the launch is not cut: a bucket that crosses a multiple
+        // of 2^32 calls (2^35 coordinates) runs with the high counter word per lane
+        if (one_stretch) { if (win) GQ_LAUNCH_K(true, true, 0, nvec); else GQ_LAUNCH_K(true, false, 0, nvec); }
+        else             { if (win) GQ_LAUNCH_K(false, true, 0, nvec); else GQ_LAUNCH_K(false, false, 0, nvec); }
         return launched();
     }
     // One launch per stretch of vectors whose Philox call index shares its high 32 bits (a second
@@ -314,22 +447,12 @@ static gq_status launch_quantize_aggregate(const GradPtrs &P, const LevelPtrs &L
         const uint64_t first = call_base + (uint64_t)v0;
         const uint64_t room = ((uint64_t)1 << 32) - (first & 0xFFFFFFFFull);
         const int64_t count = (uint64_t)(nvec - v0) < room ? (nvec - v0) : (int64_t)room;
-        if (win) {
-            if (K == 4) GQ_LAUNCH(4, false, true, true, v0, count);
-            else if (K == 8) GQ_LAUNCH(8, false, true, true, v0, count);
-            else if (K == 16) GQ_LAUNCH(16, false, true, true, v0, count);
-            else if (K == 32) GQ_LAUNCH(32, false, true, true, v0, count);
-            else GQ_LAUNCH(0, false, true, true, v0, count);
-        } else {
-            if (K == 4) GQ_LAUNCH(4, false, true, false, v0, count);
-            else if (K == 8) GQ_LAUNCH(8, false, true, false, v0, count);
-            else if (K == 16) GQ_LAUNCH(16, false, true, false, v0, count);
-            else if (K == 32) GQ_LAUNCH(32, false, true, false, v0, count);
-            else GQ_LAUNCH(0, false, true, false, v0, count);
-        }
+        if (win) GQ_LAUNCH_K(true, true, v0, count);
+        else GQ_LAUNCH_K(true, false, v0, count);
         if (launched() != GQ_OK) return GQ_ERR_DEVICE;
         v0 += count;
     }
+#undef GQ_LAUNCH_K
 #undef GQ_LAUNCH
     return GQ_OK;
 }
@@ -345,26 +468,30 @@ gq_status gq_quantize(const float *x, int64_t d, const float *norm, const gq_par
 {
     const gq_status st = check_params(p, true, false);
     if (st != GQ_OK) return st;
-    if (d < 0 || index_base < 0 || (index_base & 3) != 0) return GQ_ERR_INVALID_ARG;
+    const bool half = short_draws(p);
+    if (d < 0 || index_base < 0 || (index_base & (half ? 7 : 3)) != 0) return GQ_ERR_INVALID_ARG;
     if (!aligned(norm, 4)) return GQ_ERR_INVALID_ARG;
     const bool plane = p->pack >= GQ_PACK_U8_SIGNPLANE;
     if (d > 0 && (!aligned(x, 16) || !aligned(levels_out, 16))) return GQ_ERR_INVALID_ARG;
     if (d > 0 && plane && !aligned(signplane_out, 4)) return GQ_ERR_INVALID_ARG;
     if (d == 0) return GQ_OK;
     const int64_t nvec = (d + 3) / 4;
-    const int64_t per_block = (int64_t)kQuantBlock * kQuantVec;
+    const int64_t per_block = (int64_t)kQuantBlock * kQuantVec;          // vectors per workgroup, either mode
     const int64_t blocks = (nvec + per_block - 1) / per_block;
     if (!grid_fits(blocks)) return GQ_ERR_INVALID_ARG;
     const dim3 grid((unsigned)blocks), block(kQuantBlock);
-    const uint64_t call_base = (uint64_t)index_base / 4u;
-    // the high counter word is a scalar unless the bucket (rounded up to whole blocks) crosses 2^34
-    const bool one_stretch = ((call_base & 0xFFFFFFFFull) + (uint64_t)(blocks * per_block)) <= ((uint64_t)1 << 32);
+    const int lane_vecs = half ? 2 : 1;                                  // vectors per Philox call
+    const uint64_t call_base = (uint64_t)index_base / (uint64_t)(4 * lane_vecs);
+    // the high counter word is a scalar unless the bucket (rounded up to whole blocks) crosses 2^32 calls
+    const bool one_stretch = ((call_base & 0xFFFFFFFFull) + (uint64_t)(blocks * per_block / lane_vecs)) <= ((uint64_t)1 << 32);
     uint32_t *sp = plane ? signplane_out : nullptr;
     hipStream_t st2 = (hipStream_t)hip_stream;
-#define GQ_QUANT(SC, UH) hipLaunchKernelGGL((quantize_kernel<SC, UH>), grid, block, 0, st2, x, levels_out, sp, d, norm, \
-                                            p->s, p->seed, worker, call_base, p->pack)
-    if (p->scheme == GQ_LINEAR) { if (one_stretch) GQ_QUANT(0, true); else GQ_QUANT(0, false); }
-    else                        { if (one_stretch) GQ_QUANT(1, true); else GQ_QUANT(1, false); }
+#define GQ_QUANT(SC, UH, HF) hipLaunchKernelGGL((quantize_kernel<SC, UH, HF>), grid, block, 0, st2, x, levels_out, sp, d, norm, \
+                                                p->s, p->seed, worker, call_base, p->pack)
+#define GQ_QUANT2(SC, UH) do { if (half) GQ_QUANT(SC, UH, true); else GQ_QUANT(SC, UH, false); } while (0)
+    if (p->scheme == GQ_LINEAR) { if (one_stretch) GQ_QUANT2(0, true); else GQ_QUANT2(0, false); }
+    else                        { if (one_stretch) GQ_QUANT2(1, true); else GQ_QUANT2(1, false); }
+#undef GQ_QUANT2
 #undef GQ_QUANT
     return launched();
 }
@@ -376,7 +503,8 @@ gq_status gq_fused_quantize_aggregate(const float *const *x, int K, int64_t d, c
     const bool levels = levels_out != nullptr;
     gq_status st = check_params(p, levels, agg_out != nullptr);
     if (st != GQ_OK) return st;
-    if (!x || K < 1 || K > GQ_MAX_WORKERS || d < 0 || index_base < 0 || (index_base & 3) != 0) return GQ_ERR_INVALID_ARG;
+    const bool half = short_draws(p);
+    if (!x || K < 1 || K > GQ_MAX_WORKERS || d < 0 || index_base < 0 || (index_base & (half ? 7 : 3)) != 0) return GQ_ERR_INVALID_ARG;
     if (!agg_out && !dequant_out) return GQ_ERR_INVALID_ARG;
     if (!aligned(norm, 4)) return GQ_ERR_INVALID_ARG;
     // the sum is formed in 32-bit registers whatever is stored; a 16-bit store must also hold it
@@ -402,9 +530,13 @@ gq_status gq_fused_quantize_aggregate(const float *const *x, int K, int64_t d, c
     }
     if (d > 0 && ((agg_out && !aligned(agg_out, 16)) || (dequant_out && !aligned(dequant_out, 16)))) return GQ_ERR_INVALID_ARG;
     if (d == 0) return GQ_OK;
-    if (p->scheme == GQ_LINEAR)
-        return launch_quantize_aggregate<0>(P, L, levels, K, d, norm, p, 0u, index_base, agg_out, dequant_out, (hipStream_t)hip_stream);
-    return launch_quantize_aggregate<1>(P, L, levels, K, d, norm, p, 0u, index_base, agg_out, dequant_out, (hipStream_t)hip_stream);
+    hipStream_t hs = (hipStream_t)hip_stream;
+    if (p->scheme == GQ_LINEAR) {
+        if (half) return launch_quantize_aggregate<0, true>(P, L, levels, K, d, norm, p, 0u, index_base, agg_out, dequant_out, hs);
+        return launch_quantize_aggregate<0, false>(P, L, levels, K, d, norm, p, 0u, index_base, agg_out, dequant_out, hs);
+    }
+    if (half) return launch_quantize_aggregate<1, true>(P, L, levels, K, d, norm, p, 0u, index_base, agg_out, dequant_out, hs);
+    return launch_quantize_aggregate<1, false>(P, L, levels, K, d, norm, p, 0u, index_base, agg_out, dequant_out, hs);
 }
 
 }  // extern "C"

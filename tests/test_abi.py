@@ -70,6 +70,20 @@ def test_host_only_entry_points(gq):
     assert gq.norm_workspace_bytes(65, 10) == 0 and gq.norm_workspace_bytes(1, -1) == 0
 
 
+def test_parameter_struct_layout_matches_the_header(gq):
+    # gq_params as declared in include/gqsgd.h: six int32 then the 64-bit seed (32 bytes, seed at 24)
+    import ctypes as C
+    src = open(os.path.join(ROOT, "include", "gqsgd.h")).read()
+    body = src[src.index("typedef struct {"):src.index("} gq_params;")]
+    fields = re.findall(r"(int32_t|uint64_t)\s+(\w+);", body)
+    assert [n for _, n in fields] == ["scheme", "s", "pack", "agg", "rng_bits", "reserved", "seed"]
+    assert [n for n, _ in gq.gq_params._fields_] == [n for _, n in fields]
+    assert C.sizeof(gq.gq_params) == 32 and gq.gq_params.seed.offset == 24 and gq.gq_params.rng_bits.offset == 16
+    p = gq.make_params(1, 7, 1, 1, seed=0x1122334455667788, rng_bits=16)
+    assert (p.scheme, p.s, p.pack, p.agg, p.rng_bits, p.reserved, p.seed) == (1, 7, 1, 1, 16, 0, 0x1122334455667788)
+    assert gq.make_params(0, 5).rng_bits == 32
+
+
 def test_argument_checks_need_no_device(gq):
     """Every entry point validates its arguments on the host before anything is enqueued, so the error
     paths can be exercised without a GPU (the pointers below are never dereferenced)."""
@@ -99,11 +113,16 @@ def test_argument_checks_need_no_device(gq):
     assert q(P(gq.GQ_LINEAR, 15, gq.GQ_PACK_U4_SIGNPLANE), sp=None) == I                       # sign plane missing
     assert q(P(2, 15)) == I and q(P(gq.GQ_LINEAR, 0)) == I and q(P(gq.GQ_LINEAR, 5, 9)) == I
     assert lib.gq_quantize(fake, 16, fake, None, 0, 0, fake, None, None) == I                 # no parameters
+    # random bits per coordinate: 32 (0 reads as 32) or 16; 16 wants index_base to be a multiple of 8
+    assert q(P(gq.GQ_LINEAR, 127, rng_bits=8)) == I and q(P(gq.GQ_LINEAR, 127, rng_bits=24)) == I
+    assert q(P(gq.GQ_LINEAR, 127, rng_bits=16), base=4) == I and q(P(gq.GQ_LINEAR, 127, rng_bits=16), d=0, base=8) == gq.GQ_OK
+    assert q(P(gq.GQ_LINEAR, 127, rng_bits=0), d=0, base=4) == gq.GQ_OK and q(P(gq.GQ_LINEAR, 127, rng_bits=32), d=0, base=4) == gq.GQ_OK
     # gq_fused_quantize_aggregate
     f = lambda p, K=2, x=arr, agg=fake, deq=None, base=0: lib.gq_fused_quantize_aggregate(
         x, K, 16, fake, C.byref(p), base, agg, deq, None, None, None)
     assert f(ok, agg=None) == I and f(ok, K=0) == I and f(ok, K=65) == I and f(ok, x=bad_arr) == I
     assert f(ok, agg=odd) == I and f(ok, base=6) == I
+    assert f(P(gq.GQ_LINEAR, 127, rng_bits=16), base=12) == I and f(P(gq.GQ_LINEAR, 127, rng_bits=5)) == I
     assert f(P(gq.GQ_EXP, 15, agg=gq.GQ_AGG_I16), K=2, x=None) == I
     big = (C.c_void_p * 32)(*([0x1000] * 32))
     assert f(P(gq.GQ_EXP, 15, agg=gq.GQ_AGG_I16), K=32, x=big) == gq.GQ_ERR_OVERFLOW

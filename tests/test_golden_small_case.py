@@ -27,7 +27,7 @@ def test_oracle_reproduces_the_stored_case():
     _, nf, _ = O.global_norm(xs, O.NORM_LINF)
     for run in CASE["runs"]:
         sc, s, pk = SCH[run["scheme"]], run["s"], PK[run["pack"]]
-        qs = [O.quantize(xs[i], nf, sc, s, seed, i, base) for i in range(K)]
+        qs = [O.quantize(xs[i], nf, sc, s, seed, i, base, rng_bits=run["rng_bits"]) for i in range(K)]
         assert [q.tolist() for q in qs] == run["codes"]
         for i, q in enumerate(qs):
             lv, sp = O.pack(q, pk)
@@ -63,7 +63,7 @@ def test_library_reproduces_the_stored_case():
     gq.global_norm(xs, 0, norm, flags)
     for run in CASE["runs"]:
         sc, s, pk = SCH[run["scheme"]], run["s"], PK[run["pack"]]
-        p = gq.make_params(sc, s, pk, gq.GQ_AGG_I32, seed=seed)
+        p = gq.make_params(sc, s, pk, gq.GQ_AGG_I32, seed=seed, rng_bits=run["rng_bits"])
         agg = torch.zeros(d, dtype=torch.int32, device=dev)
         deq = torch.zeros(d, device=dev)
         lvs = [torch.zeros(gq.levels_nbytes(d, pk), dtype=torch.uint8, device=dev) for _ in range(K)]

@@ -370,6 +370,102 @@ def test_fused_across_the_2_to_34_index_boundary():
     assert np.array_equal(host(agg_out)[:d].astype(np.int64), want)
 
 
+# ------------------------------------------------------------------------------------ short draws
+# 16 random bits per coordinate, one Philox call per eight coordinates: a lane owns two vectors.
+@pytest.mark.parametrize("scheme,s,pack", [("linear", 127, "i8"), ("linear", 7, "i4"), ("linear", 255, "u8s"),
+                                           ("linear", 15, "u4s"), ("exp", 16, "i8"), ("exp", 7, "i4"),
+                                           ("exp", 31, "u8s"), ("exp", 15, "u4s")])
+@pytest.mark.parametrize("d", [1, 2, 3, 4, 5, 6, 7, 8, 9, 12, 13, 31, 32, 33, 63, 64, 65, 255, 1021, 4099, 70_001, 70_004])
+def test_quantize_short_draws_matches_oracle(scheme, s, pack, d):
+    x = gaussians(1, d, seed=d + s + 1)[0]
+    xh = host(x)
+    _, nf, _ = oracle_norm([x], NORMS["linf"])
+    norm_t = dev_scalar(float(nf))
+    params = gq.make_params(SCHEMES[scheme], s, PACKS[pack], 0, seed=SI.QUANT_SEED, rng_bits=16)
+    for worker, base in [(0, 0), (3, 8 * 1234567), (17, 1 << 37), (5, (1 << 35) - 8 * 100)]:
+        lv, sp = gpu_quantize(x, norm_t, params, worker, base)
+        q = O.quantize(xh, nf, SCHEMES[scheme], s, SI.QUANT_SEED, worker, base, rng_bits=16)
+        want_lv, want_sp = O.pack(q, PACKS[pack])
+        n = want_lv.shape[0]
+        got = host(lv)
+        assert np.array_equal(got[:n], want_lv)
+        assert np.all(got[n:] == 0xAB)
+        if want_sp is not None:
+            gs = host(sp).view(np.uint32)
+            assert np.array_equal(gs[:want_sp.shape[0]], want_sp)
+            assert np.all(gs[want_sp.shape[0]:] == 0xFFFFFFFF)
+
+
+@pytest.mark.parametrize("scheme,s,pack,agg", [("linear", 127, "i8", 0), ("linear", 15, "u4s", 0), ("linear", 7, "i4", 1),
+                                               ("exp", 16, "i8", 0), ("exp", 7, "i4", 1), ("exp", 9, "u8s", 1)])
+@pytest.mark.parametrize("K,d", [(1, 4099), (2, 3), (2, 5), (3, 70_001), (4, 70_006), (5, 1021), (8, 70_003), (16, 70_000),
+                                 (32, 8191), (33, 513), (64, 1004)])
+def test_fused_short_draws_matches_oracle(scheme, s, pack, agg, K, d):
+    params = gq.make_params(SCHEMES[scheme], s, PACKS[pack], agg, seed=SI.QUANT_SEED + K, rng_bits=16)
+    if gq.check_width(params, K) != gq.GQ_OK:
+        pytest.skip("sum does not fit the width (covered by the error tests)")
+    xs = gaussians(K, d, seed=K * 11 + d)
+    xh = [host(x) for x in xs]
+    _, nf, _ = oracle_norm(xs, NORMS["linf"])
+    norm_t = dev_scalar(float(nf))
+    base = 8 * 98765
+    want = O.quantize_aggregate(xh, nf, SCHEMES[scheme], s, params.seed, base, rng_bits=16)
+    assert not np.array_equal(want, O.quantize_aggregate(xh, nf, SCHEMES[scheme], s, params.seed, base)) or d < 8
+    want_deq = O.dequantize(want, float(nf), SCHEMES[scheme], s, K)
+    for with_levels in (False, True):
+        agg_out, deq_out, lvs, sps = run_fused(xs, norm_t, params, base, with_levels)
+        got = host(agg_out)
+        assert np.array_equal(got[:d].astype(np.int64), want) and np.all(got[d:] == 0x5A5A)
+        gd = host(deq_out).astype(np.float64)
+        assert np.all(np.abs(gd[:d] - want_deq) <= RTOL * np.abs(want_deq))
+        assert np.all(gd[:d][want == 0] == 0.0) and np.all(gd[d:] == 7.0)
+        if with_levels:
+            for i in range(K):
+                q = O.quantize(xh[i], nf, SCHEMES[scheme], s, params.seed, i, base, rng_bits=16)
+                wl, ws = O.pack(q, PACKS[pack])
+                gl = host(lvs[i])
+                assert np.array_equal(gl[:wl.shape[0]], wl) and np.all(gl[wl.shape[0]:] == 0xAB)
+                if ws is not None:
+                    gs = host(sps[i]).view(np.uint32)
+                    assert np.array_equal(gs[:ws.shape[0]], ws) and np.all(gs[ws.shape[0]:] == 0xFFFFFFFF)
+
+
+def test_short_draws_buckets_boundary_and_separate_calls():
+    K, d = 8, 300_011
+    xs = gaussians(K, d, seed=78)
+    xh = [host(x) for x in xs]
+    for scheme, s, pack in [("linear", 127, "i8"), ("exp", 7, "i4"), ("linear", 15, "u4s")]:
+        params = gq.make_params(SCHEMES[scheme], s, PACKS[pack], 0, seed=6, rng_bits=16)
+        norm_t = dev_scalar(0.0)
+        gq.global_norm(xs, NORMS["linf"], norm_t)
+        whole, whole_deq, _, _ = run_fused(xs, norm_t, params, 0, False)
+        lvs, sps = [], []
+        for i in range(K):
+            lv, sp = gpu_quantize(xs[i], norm_t, params, i, 0)
+            lvs.append(lv); sps.append(sp)
+        agg = torch.zeros(d, dtype=torch.int32, device=DEV)
+        gq.int_aggregate(lvs, sps if sps[0] is not None else None, d, params, agg)
+        torch.cuda.synchronize()
+        assert torch.equal(agg, whole[:d])
+        cut = [0, 8 * 10_001, 8 * 20_000, d]
+        for lo, hi in zip(cut[:-1], cut[1:]):
+            part, _, _, _ = run_fused([x[lo:hi] for x in xs], norm_t, params, lo, False)
+            assert torch.equal(part[:hi - lo], whole[lo:hi])
+    # the Philox call index g/8 crosses a multiple of 2^32 inside the bucket
+    _, nf, _ = oracle_norm(xs, NORMS["linf"])
+    norm_t = dev_scalar(float(nf))
+    d2 = 70_001
+    params = gq.make_params(0, 127, 0, 0, seed=31337, rng_bits=16)
+    for base in ((1 << 35) - 8 * 1000, (1 << 35) - 8 * 129, (1 << 35) - 8, 1 << 35, 3 * (1 << 35) - 8 * 8_000):
+        want = O.quantize_aggregate([x[:d2] for x in xh], nf, 0, 127, params.seed, base, rng_bits=16)
+        for with_levels in (False, True):
+            agg_out, _, _, _ = run_fused([x[:d2] for x in xs], norm_t, params, base, with_levels)
+            assert np.array_equal(host(agg_out)[:d2].astype(np.int64), want)
+        want5 = O.quantize_aggregate([x[:d2] for x in xh[:5]], nf, 0, 127, params.seed, base, rng_bits=16)
+        agg_out, _, _, _ = run_fused([x[:d2] for x in xs[:5]], norm_t, params, base, False)
+        assert np.array_equal(host(agg_out)[:d2].astype(np.int64), want5)
+
+
 # ------------------------------------------------------------------------------------ Algorithm 2
 @pytest.mark.parametrize("K", [1, 2, 3, 4, 5, 8, 13, 16, 32, 33, 64])
 @pytest.mark.parametrize("s,d", [(7, 70_003), (16, 4099), (31, 1021), (1, 255)])
@@ -622,18 +718,20 @@ def test_unbiased_on_gpu_monte_carlo():
 
 
 # ------------------------------------------------------------------------------------ workloads
-def check_windows(xs, agg, nf, scheme, s, seed, windows, width):
+def check_windows(xs, agg, nf, scheme, s, seed, windows, width, rng_bits=32):
     d = xs[0].numel()
     for lo in windows:
-        lo = max(0, min(lo, d - width)) & ~3
+        lo = max(0, min(lo, d - width)) & ~7
         hi = min(d, lo + width)
-        want = O.quantize_aggregate([host(x[lo:hi]) for x in xs], nf, scheme, s, seed, lo)
+        want = O.quantize_aggregate([host(x[lo:hi]) for x in xs], nf, scheme, s, seed, lo, rng_bits=rng_bits)
         assert np.array_equal(host(agg[lo:hi]).astype(np.int64), want), "window at %d" % lo
 
 
-@pytest.mark.parametrize("scheme,s,agg_fmt,K,d", [(0, 127, 0, 12, 21_000_003), (1, 7, 1, 24, 10_500_001),
-                                                  (0, 63, 0, 8, 31_300_002), (1, 12, 0, 19, 13_200_001)])
-def test_fused_large_launches_equal_small_buckets_and_oracle(scheme, s, agg_fmt, K, d):
+@pytest.mark.parametrize("scheme,s,agg_fmt,K,d,rng_bits", [(0, 127, 0, 12, 21_000_003, 32), (1, 7, 1, 24, 10_500_001, 32),
+                                                           (0, 63, 0, 8, 31_300_002, 32), (1, 12, 0, 19, 13_200_001, 32),
+                                                           (0, 127, 0, 16, 16_000_005, 16), (1, 7, 1, 32, 8_000_003, 16),
+                                                           (0, 15, 0, 11, 23_000_001, 16)])
+def test_fused_large_launches_equal_small_buckets_and_oracle(scheme, s, agg_fmt, K, d, rng_bits):
     # Launches with K * d >= 2.5e8 take the kernel variant that bounds its loads in flight and stores
     # inside time windows; the same gradient cut into buckets below that size takes the plain variant.
     # Both must give the same integers, and those of the oracle on sampled windows.
@@ -642,7 +740,7 @@ def test_fused_large_launches_equal_small_buckets_and_oracle(scheme, s, agg_fmt,
     mx = max(float(x.abs().max()) for x in xs)
     nf = np.float32(mx)
     norm_t = dev_scalar(float(nf))
-    params = gq.make_params(scheme, s, 0, agg_fmt, seed=SI.QUANT_SEED + 1)
+    params = gq.make_params(scheme, s, 0, agg_fmt, seed=SI.QUANT_SEED + 1, rng_bits=rng_bits)
     adt = torch.int16 if agg_fmt == 1 else torch.int32
     whole = torch.full((d + 8,), 0x5A5A, dtype=adt, device=DEV)
     whole_deq = torch.full((d + 8,), 7.0, device=DEV)
@@ -659,7 +757,7 @@ def test_fused_large_launches_equal_small_buckets_and_oracle(scheme, s, agg_fmt,
     assert bool((whole[d:] == 0x5A5A).all()) and bool((whole_deq[d:] == 7.0).all())
     rng = np.random.default_rng(K)
     wins = [0, d - (1 << 15)] + [int(v) for v in rng.integers(0, d - (1 << 15), 6)]
-    check_windows(xs, whole[:d], nf, scheme, s, params.seed, wins, 1 << 15)
+    check_windows(xs, whole[:d], nf, scheme, s, params.seed, wins, 1 << 15, rng_bits=rng_bits)
 
 
 def test_workload_c1_full_parity():
