@@ -67,10 +67,17 @@ def cpu_baseline(xs, nf, scheme, s, seed, sample, bytes_per_coord):
     with ThreadPoolExecutor(max_workers=threads) as ex:
         parts = list(ex.map(work, cuts))
     dt = time.perf_counter() - t0
+    # and on one thread, on a sixteenth of the sample
+    one = max(4, (sample // 16) & ~3)
+    t1 = time.perf_counter()
+    O.quantize_aggregate([h[:one] for h in host], nf, scheme, s, seed, 0)
+    dt1 = time.perf_counter() - t1
     return {
         "value": sample * bytes_per_coord / dt * 1e-9, "unit": "GB/s", "cores": min(threads, len(cuts)),
         "kind": "oracle", "seconds": dt, "coords_per_s": sample / dt,
         "sample": "first %d of %d coordinates of all %d workers (same buffers, same accounting)" % (sample, d, len(xs)),
+        "single_thread": {"value": one * bytes_per_coord / dt1 * 1e-9, "unit": "GB/s", "coords_per_s": one / dt1,
+                          "seconds": dt1, "sample": "first %d coordinates of all %d workers" % (one, len(xs))},
     }, parts, cuts
 
 
@@ -238,12 +245,14 @@ def main():
     fused_gbps = b_fused / fused_ms * 1e-6
     step_gbps = (b_norm + b_fused + b_deq) / ms_per_step * 1e-6
 
-    traffic = None
+    traffic = valu_busy = None
     if args.workload == "c3" and os.path.exists(TRAFFIC_FILE):
         try:
-            traffic = json.load(open(TRAFFIC_FILE)).get("hbm_bytes_per_launch")
+            prof = json.load(open(TRAFFIC_FILE))
+            traffic = prof.get("hbm_bytes_per_launch")
+            valu_busy = prof.get("valu_busy_frac")          # from the SQ counters of the same command
         except Exception:
-            traffic = None
+            traffic = valu_busy = None
 
     line = {
         "metric": ("fused quantize+aggregate GB/s and % of HBM peak, d=110M K=16 fp32" if args.workload == "c3" else
@@ -260,7 +269,8 @@ def main():
         "roofline": {"bound": "hbm", "achieved": fused_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": fused_gbps / HBM_PEAK_GBPS, "traffic": traffic,
                      "kernel": "quantize_aggregate_kernel", "algorithmic_bytes_per_launch": b_fused,
-                     "avg_ms": fused_ms, "min_ms": float(np.min(t_fused))},
+                     "avg_ms": fused_ms, "median_ms": float(np.median(t_fused)), "min_ms": float(np.min(t_fused)),
+                     "valu_busy_frac_profiled": valu_busy},
         "step_GBps": step_gbps, "step_algorithmic_bytes": b_norm + b_fused + b_deq, "wall_ms_per_step": wall_ms / args.steps,
         "calls_ms": {"global_norm": float(np.mean(t_norm)), "fused_quantize_aggregate": fused_ms,
                      "dequantize": float(np.mean(t_deq))},
@@ -297,6 +307,7 @@ def main():
                 torch.cuda.synchronize()
             got = agg[:cuts[-1][1]].cpu().numpy().astype(np.int64)
             base["matches_gpu"] = bool(all(np.array_equal(got[lo:hi], p) for (lo, hi), p in zip(cuts, parts)))
+        base["gpu_over_cpu"] = fused_gbps / base["value"]
         line["cpu_baseline"] = base
     print(json.dumps(line))
 

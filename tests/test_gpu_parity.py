@@ -799,9 +799,10 @@ def test_workload_c3_sampled_parity_at_bench_shape():
     agg = torch.empty(d, dtype=torch.int32, device=DEV)
     gq.fused_quantize_aggregate(xs, norm_t, params, 0, agg)
     torch.cuda.synchronize()
+    # the oracle on the first and the last 2^20 coordinates and on 64 random windows of 2^16
     rng = np.random.default_rng(3)
-    wins = [0, d - (1 << 16)] + [int(v) for v in rng.integers(0, d - (1 << 16), 24)]
-    check_windows(xs, agg, nf, 0, 127, SI.QUANT_SEED, wins, 1 << 16)
+    check_windows(xs, agg, nf, 0, 127, SI.QUANT_SEED, [0, d - (1 << 20)], 1 << 20)
+    check_windows(xs, agg, nf, 0, 127, SI.QUANT_SEED, [int(v) for v in rng.integers(0, d - (1 << 16), 64)], 1 << 16)
     # properties that hold at any size: bound by n*s, sign pattern, and the sum of the sums against
     # the exact expectation s/norm * sum_i sum_j x_ij within 6 standard deviations
     assert int(agg.abs().max()) <= K * 127

@@ -26,10 +26,15 @@ def host(t):
     return t.detach().cpu().numpy()
 
 
-def windows(d, width, n, seed, extra=()):
+def spans(d, seed, edges=()):
+    """The index ranges on which the oracle is evaluated at full size: the first and the last 2^20
+    coordinates, 64 random windows of 2^16, and 4096 coordinates either side of every edge given
+    (bucket or block boundaries).  Starts are multiples of 8 so that any draw mode can be replayed."""
     rng = np.random.default_rng(seed)
-    w = [0, d - width] + [int(v) for v in rng.integers(0, d - width, n)] + list(extra)
-    return sorted(set(max(0, min(int(lo), d - width)) & ~3 for lo in w))
+    out = [(0, min(d, 1 << 20)), (max(0, d - (1 << 20)) & ~7, d)]
+    out += [(int(lo) & ~7, min(d, (int(lo) & ~7) + (1 << 16))) for lo in rng.integers(0, max(1, d - (1 << 16)), 64)]
+    out += [(max(0, int(e) - 4096) & ~7, min(d, int(e) + 4096)) for e in edges]
+    return sorted(set(out))
 
 
 def torch_norm(xs, kind):
@@ -66,10 +71,8 @@ def test_workload_c2_layer_blocks_exponential_int8():
     torch.cuda.synchronize()
     assert torch.equal(agg, fagg) and torch.equal(deq, fdeq)
     assert all(torch.equal(a, b) for a, b in zip(lvs, flv))
-    width = 1 << 15
     per_block = d // cfg["blocks"]
-    for lo in windows(d, width, 12, 2, extra=[per_block * b - width // 2 for b in (1, 57, 159)]):
-        hi = lo + width
+    for lo, hi in spans(d, 2, edges=[per_block * b for b in (1, 57, 159)]):
         xh = [host(x[lo:hi]) for x in xs]
         want = O.quantize_aggregate(xh, nf, O.EXP, s, SI.QUANT_SEED, lo)
         assert np.array_equal(host(agg[lo:hi]).astype(np.int64), want), lo
@@ -111,9 +114,7 @@ def test_workload_c4_student_t_exponential_int4_int16():
     gq.fused_quantize_aggregate(xs, norm_t, p, 0, fagg)
     torch.cuda.synchronize()
     assert torch.equal(agg, fagg)
-    width = 1 << 14
-    for lo in windows(d, width, 10, 4):
-        hi = lo + width
+    for lo, hi in spans(d, 4):
         xh = [host(x[lo:hi]) for x in xs]
         want = O.quantize_aggregate(xh, nf, O.EXP, s, SI.QUANT_SEED, lo)
         assert O.fits_width(want, 16)
@@ -150,10 +151,7 @@ def test_workload_c5_bucketed_fused_quantize_aggregate_dequantize():
     torch.cuda.synchronize()
     assert torch.equal(out, whole)                                               # bucketed == unbucketed
     del whole
-    width = 8192
-    edges = [b * bucket - width // 2 for b in range(1, nb)]
-    for lo in windows(d, width, 8, 5, extra=edges):
-        hi = lo + width
+    for lo, hi in spans(d, 5, edges=[b * bucket for b in range(1, nb)]):
         xh = [host(x[lo:hi]) for x in xs]
         A = O.quantize_aggregate(xh, nf, O.LINEAR, s, SI.QUANT_SEED, lo)
         wd = O.dequantize(A, float(nf), O.LINEAR, s, K)
