@@ -95,6 +95,7 @@ template <> struct Round<0> {
         return __builtin_copysignf(c, x);
     }
     static __device__ __forceinline__ int code_of_value(float value) { return (int)value; }
+    static __device__ __forceinline__ int code(float x, const Scale &sc, uint32_t r) { return (int)value(x, sc, r); }
 };
 
 // Exponential grid {0} u {2^-j}: z = y*2^(s-1); a binary32 z >= 1 is rounded to a neighbouring power of
@@ -115,6 +116,17 @@ template <> struct Round<1> {
         const uint32_t b = __float_as_uint(value);
         const int k = max((int)((b >> 23) & 0xFFu) - 126, 0);
         return (b >> 31) ? -k : k;
+    }
+    // The code without the detour over the value: the rounded w = z (+1 if z < 1) has exponent field E, and
+    // k = E - 126 for z >= 1 (value 2^(E-127)), k = E - 127 for z < 1 (value 0 or 1).
+    static __device__ __forceinline__ int code(float x, const Scale &sc, uint32_t r)
+    {
+        const float z = __builtin_fminf(__builtin_fabsf(x) * sc.scale, sc.top);
+        const bool small = z < 1.0f;
+        const float w = z + (small ? 1.0f : 0.0f);
+        const uint32_t b = __float_as_uint(w) + (r >> 9);
+        const int k = (int)(b >> 23) - (small ? 127 : 126);
+        return x < 0.0f ? -k : k;
     }
 };
 

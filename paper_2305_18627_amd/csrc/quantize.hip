@@ -49,24 +49,37 @@ __device__ __forceinline__ uint32_t or_over_8_lanes(uint32_t v)
     return v;
 }
 
+// The four sign bits of a lane's codes; the codes are replaced by their magnitudes.
+__device__ __forceinline__ uint32_t sign_nibble(int *q)
+{
+    uint32_t nib = 0;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        nib |= (uint32_t)(q[i] < 0) << i;
+        q[i] = abs(q[i]);
+    }
+    return nib;
+}
+__device__ __forceinline__ uint32_t pack_bytes(const int *q)
+{
+    return (uint32_t)(q[0] & 255) | ((uint32_t)(q[1] & 255) << 8) | ((uint32_t)(q[2] & 255) << 16) | ((uint32_t)(q[3] & 255) << 24);
+}
+__device__ __forceinline__ uint32_t pack_nibbles(const int *q)
+{
+    return (uint32_t)(q[0] & 15) | ((uint32_t)(q[1] & 15) << 4) | ((uint32_t)(q[2] & 15) << 8) | ((uint32_t)(q[3] & 15) << 12);
+}
+
 // Store the codes q[0..3] of vector v (nvalid of its coordinates exist).  The lanes of a wave must hold
 // consecutive vectors, lane 0 a multiple of 8, and all be active (the sign words are assembled across lanes).
 __device__ __forceinline__ void store_codes(void *lv, uint32_t *sp, int pack, int64_t v, int nvalid, int64_t d, int *q)
 {
     if (pack >= 2) {
-        uint32_t nib = 0;
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-            nib |= (uint32_t)(q[i] < 0) << i;
-            q[i] = abs(q[i]);
-        }
-        const uint32_t word = or_over_8_lanes(nib << (4 * (threadIdx.x & 7)));
+        const uint32_t word = or_over_8_lanes(sign_nibble(q) << (4 * (threadIdx.x & 7)));
         if ((threadIdx.x & 7) == 0 && ((v & ~(int64_t)7) << 2) < d) sp[v >> 3] = word;
     }
     if (nvalid == 0) return;
     if (pack == GQ_PACK_I8 || pack == GQ_PACK_U8_SIGNPLANE) {
-        const uint32_t w = (uint32_t)(q[0] & 255) | ((uint32_t)(q[1] & 255) << 8) | ((uint32_t)(q[2] & 255) << 16) |
-                           ((uint32_t)(q[3] & 255) << 24);
+        const uint32_t w = pack_bytes(q);
         if (nvalid == 4) {
             __builtin_nontemporal_store(w, reinterpret_cast<uint32_t *>(lv) + v);
         } else {
@@ -74,8 +87,7 @@ __device__ __forceinline__ void store_codes(void *lv, uint32_t *sp, int pack, in
             for (int i = 0; i < nvalid; i++) b[i] = (uint8_t)(w >> (8 * i));
         }
     } else {
-        const uint32_t w = (uint32_t)(q[0] & 15) | ((uint32_t)(q[1] & 15) << 4) | ((uint32_t)(q[2] & 15) << 8) |
-                           ((uint32_t)(q[3] & 15) << 12);
+        const uint32_t w = pack_nibbles(q);
         if (nvalid == 4) {
             __builtin_nontemporal_store((uint16_t)w, reinterpret_cast<uint16_t *>(lv) + v);
         } else {
@@ -321,60 +333,82 @@ quantize_aggregate_kernel(GradPtrs P, LevelPtrs L, int K, int64_t d, int64_t v0,
 constexpr int kQuantBlock = 128;
 constexpr int kQuantVec = 4;
 
-template <int SCHEME, bool UNIFORM_HI, bool HALF>
-__global__ void __launch_bounds__(kQuantBlock)
-quantize_kernel(const float *__restrict__ x, void *__restrict__ lv, uint32_t *__restrict__ sp, int64_t d,
-                const float *__restrict__ norm, int s, uint64_t seed, uint32_t worker, uint64_t call_base, int pack)
+// The work of one workgroup.  WHOLE: its kQuantBlock * kQuantVec vectors all lie inside the buffer; the loads
+// need no guards and the code words are staged in LDS and written out as one run, 16 (bytes) or 8 (nibbles)
+// bytes per thread, instead of four narrow stores per thread.  Otherwise (the ragged last workgroup) every
+// vector is guarded and stored on its own.
+template <int SCHEME, bool UNIFORM_HI, bool HALF, bool WHOLE>
+__device__ __forceinline__ void quantize_block(const float *__restrict__ x, void *__restrict__ lv, uint32_t *__restrict__ sp,
+                                               int64_t d, const Scale &sc, uint64_t seed, uint32_t worker,
+                                               uint64_t call_base, int pack, uint32_t *stage, uint32_t *stage_signs)
 {
+    constexpr int kBlockVecs = kQuantBlock * kQuantVec;
     const int64_t nfull = d >> 2;
     const int lane = (int)(threadIdx.x & 63u);
-    const Scale sc = make_scale<SCHEME>(*norm, s);
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
-    // vector j of this lane and the Philox call that it runs for vectors j, j+1 (short draws) or j (full)
-    int64_t v[kQuantVec];
-    int64_t call[kQuantVec];
+    const int64_t vblock = (int64_t)blockIdx.x * kBlockVecs;          // scalar
+    // vector j of this lane within the workgroup, and the Philox call (relative to the workgroup's first) that
+    // it runs for vectors j, j+1 (short draws) or j (full draws)
+    int li[kQuantVec];
+    int lcall[kQuantVec];
 #pragma unroll
     for (int j = 0; j < kQuantVec; j++) {
         if (HALF) {
             // the workgroup's 512 vectors are four chunks of 128; wave w takes chunks w and w + 2
-            const int64_t chunk = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6) + 2 * (j >> 1);
-            v[j] = chunk * 128 + 64 * (j & 1) + lane;
-            call[j] = chunk * 64 + (lane >> 1) + (lane & 1) * 32;
+            const int chunk = (int)(threadIdx.x >> 6) + 2 * (j >> 1);
+            li[j] = chunk * 128 + 64 * (j & 1) + lane;
+            lcall[j] = chunk * 64 + (lane >> 1) + (lane & 1) * 32;
         } else {
-            v[j] = (int64_t)blockIdx.x * (kQuantBlock * kQuantVec) + (int64_t)j * kQuantBlock + threadIdx.x;
-            call[j] = v[j];
+            li[j] = j * kQuantBlock + (int)threadIdx.x;
+            lcall[j] = li[j];
         }
     }
+    const float *xb = x + (vblock << 2);
     f32x4 g[kQuantVec];
     int nvalid[kQuantVec];
 #pragma unroll
     for (int j = 0; j < kQuantVec; j++) {
-        nvalid[j] = v[j] < nfull ? 4 : (v[j] == nfull ? (int)(d & 3) : 0);
-        g[j] = load_coords(x, v[j], nvalid[j]);
-    }
-    auto counter = [&](int64_t c, uint32_t &c_lo, uint32_t &c_hi) {
-        if (UNIFORM_HI) {                             // host: call_base + c stays below the next multiple of 2^32
-            c_hi = (uint32_t)(call_base >> 32);
-            c_lo = (uint32_t)call_base + (uint32_t)c;
+        if (WHOLE) {
+            nvalid[j] = 4;
+            g[j] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(xb) + li[j]);
         } else {
-            const uint64_t cc = call_base + (uint64_t)c;
+            const int64_t v = vblock + li[j];
+            nvalid[j] = v < nfull ? 4 : (v == nfull ? (int)(d & 3) : 0);
+            g[j] = load_coords(x, v, nvalid[j]);
+        }
+    }
+    const uint64_t first = call_base + (uint64_t)(HALF ? (vblock >> 1) : vblock);    // scalar
+    auto counter = [&](int c, uint32_t &c_lo, uint32_t &c_hi) {
+        if (UNIFORM_HI) {                             // host: the launch stays below the next multiple of 2^32 calls
+            c_hi = (uint32_t)(first >> 32);
+            c_lo = (uint32_t)first + (uint32_t)c;
+        } else {
+            const uint64_t cc = first + (uint64_t)c;
             c_lo = (uint32_t)cc;
             c_hi = (uint32_t)(cc >> 32);
         }
     };
+    const bool bytes = pack == GQ_PACK_I8 || pack == GQ_PACK_U8_SIGNPLANE;
     auto emit = [&](int j, const uint32_t *draw) {
-        int q[4] = {Round<SCHEME>::code_of_value(Round<SCHEME>::value(g[j].x, sc, draw[0])),
-                    Round<SCHEME>::code_of_value(Round<SCHEME>::value(g[j].y, sc, draw[1])),
-                    Round<SCHEME>::code_of_value(Round<SCHEME>::value(g[j].z, sc, draw[2])),
-                    Round<SCHEME>::code_of_value(Round<SCHEME>::value(g[j].w, sc, draw[3]))};
-        store_codes(lv, sp, pack, v[j], nvalid[j], d, q);
+        int q[4] = {Round<SCHEME>::code(g[j].x, sc, draw[0]), Round<SCHEME>::code(g[j].y, sc, draw[1]),
+                    Round<SCHEME>::code(g[j].z, sc, draw[2]), Round<SCHEME>::code(g[j].w, sc, draw[3])};
+        if (!WHOLE) {
+            store_codes(lv, sp, pack, vblock + li[j], nvalid[j], d, q);
+            return;
+        }
+        if (pack >= 2) {
+            const uint32_t word = or_over_8_lanes(sign_nibble(q) << (4 * (threadIdx.x & 7)));
+            if ((threadIdx.x & 7) == 0) stage_signs[li[j] >> 3] = word;
+        }
+        if (bytes) stage[li[j]] = pack_bytes(q);
+        else reinterpret_cast<uint16_t *>(stage)[li[j]] = (uint16_t)pack_nibbles(q);
     };
     // no lane leaves early: the sign-plane exchange and the exchange of short draws need whole waves
     if (HALF) {
 #pragma unroll
         for (int j = 0; j < kQuantVec; j += 2) {
             uint32_t c_lo, c_hi;
-            counter(call[j], c_lo, c_hi);
+            counter(lcall[j], c_lo, c_hi);
             const ShortDraws sd = share_short_draws(philox4x32_10(c_lo, c_hi, worker, 0u, k0, k1), (lane & 1) != 0);
             uint32_t da[4], db[4];
 #pragma unroll
@@ -386,11 +420,36 @@ quantize_kernel(const float *__restrict__ x, void *__restrict__ lv, uint32_t *__
 #pragma unroll
         for (int j = 0; j < kQuantVec; j++) {
             uint32_t c_lo, c_hi;
-            counter(call[j], c_lo, c_hi);
+            counter(lcall[j], c_lo, c_hi);
             const Words4 r = philox4x32_10(c_lo, c_hi, worker, 0u, k0, k1);
             emit(j, r.w);
         }
     }
+    if (WHOLE) {
+        __syncthreads();
+        const int t = (int)threadIdx.x;
+        if (bytes) {
+            const u32x4 w = *reinterpret_cast<const u32x4 *>(&stage[4 * t]);
+            __builtin_nontemporal_store(w, reinterpret_cast<u32x4 *>(lv) + (vblock / 4 + t));
+        } else {
+            const uint64_t w = *reinterpret_cast<const uint64_t *>(reinterpret_cast<const uint16_t *>(stage) + 4 * t);
+            __builtin_nontemporal_store(w, reinterpret_cast<uint64_t *>(lv) + (vblock / 4 + t));
+        }
+        if (pack >= 2 && t < kBlockVecs / 8) sp[vblock / 8 + t] = stage_signs[t];
+    }
+}
+
+template <int SCHEME, bool UNIFORM_HI, bool HALF>
+__global__ void __launch_bounds__(kQuantBlock)
+quantize_kernel(const float *__restrict__ x, void *__restrict__ lv, uint32_t *__restrict__ sp, int64_t d,
+                const float *__restrict__ norm, int s, uint64_t seed, uint32_t worker, uint64_t call_base, int pack)
+{
+    __shared__ uint32_t stage[kQuantBlock * kQuantVec];              // one code word per vector
+    __shared__ uint32_t stage_signs[kQuantBlock * kQuantVec / 8];    // one sign word per 8 vectors
+    const Scale sc = make_scale<SCHEME>(*norm, s);
+    const bool whole = ((int64_t)blockIdx.x + 1) * (kQuantBlock * kQuantVec) <= (d >> 2);   // uniform over the workgroup
+    if (whole) quantize_block<SCHEME, UNIFORM_HI, HALF, true>(x, lv, sp, d, sc, seed, worker, call_base, pack, stage, stage_signs);
+    else quantize_block<SCHEME, UNIFORM_HI, HALF, false>(x, lv, sp, d, sc, seed, worker, call_base, pack, stage, stage_signs);
 }
 
 template <int SCHEME, bool HALF>
