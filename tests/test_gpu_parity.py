@@ -212,6 +212,20 @@ def test_argument_errors():
                                                ("exp", 9, "u8s", 1), ("exp", 15, "u4s", 0)])
 @pytest.mark.parametrize("K,d", [(1, 1), (2, 15), (3, 16), (4, 17), (5, 31), (16, 32), (7, 33), (32, 4097), (6, 65_537)])
 def test_int_aggregate_matches_oracle(scheme, s, pack, agg, K, d):
+    check_int_aggregate(scheme, s, pack, agg, K, d)
+
+
+# packed 4-bit codes: workgroups of 1024 coordinates take the eight-coordinates-per-lane kernel, the rest
+# the general one; both widths of the sum, every split of K into batches of 8, 4, 2, 1
+@pytest.mark.parametrize("scheme,s,pack", [("linear", 7, "i4"), ("exp", 7, "i4"), ("exp", 3, "i4"), ("linear", 15, "u4s"),
+                                           ("linear", 1, "u4s"), ("exp", 15, "u4s")])
+@pytest.mark.parametrize("agg", [0, 1])
+@pytest.mark.parametrize("K,d", [(1, 1024), (2, 1025), (7, 6143), (13, 2048), (15, 70_001), (64, 3073), (33, 1023 + 4096)])
+def test_int_aggregate_packed_nibbles(scheme, s, pack, agg, K, d):
+    check_int_aggregate(scheme, s, pack, agg, K, d)
+
+
+def check_int_aggregate(scheme, s, pack, agg, K, d):
     rng = np.random.default_rng(K * 1000 + d + s)
     qs = [rng.integers(-s, s + 1, d).astype(np.int32) for _ in range(K)]
     qs[0][:] = s                                                 # a worker stuck at the top level
