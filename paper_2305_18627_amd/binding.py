@@ -99,6 +99,41 @@ def _check(st, where):
         raise GQError(st, where)
 
 
+# The C ABI takes raw pointers and cannot see buffer sizes; the checks below are the binding's part of the
+# contract: a tensor that is too small, not contiguous or not on the GPU is refused here, before any launch.
+def _need(t, nbytes, what):
+    if t is None:
+        return
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("%s must be a contiguous CUDA tensor" % what)
+    have = t.numel() * t.element_size()
+    if have < nbytes:
+        raise ValueError("%s holds %d bytes, the call needs %d" % (what, have, nbytes))
+
+
+def _need_grads(xs):
+    d = xs[0].numel() if xs else 0
+    for x in xs:
+        if x.dtype != torch.float32 or x.numel() != d:
+            raise ValueError("gradients must be float32 tensors of equal length")
+        _need(x, 4 * d, "gradient")
+    return d
+
+
+def _agg_bytes(params):
+    return 2 if params.agg == GQ_AGG_I16 else 4
+
+
+def _need_levels(levels, signplanes, d, params, what="levels"):
+    if levels is None:
+        return
+    for t in levels:
+        _need(t, levels_nbytes(d, params.pack), what)
+    if params.pack >= GQ_PACK_U8_SIGNPLANE and signplanes is not None:
+        for t in signplanes:
+            _need(t, 4 * signplane_nwords(d), "sign plane")
+
+
 def make_params(scheme, s, pack=GQ_PACK_I8, agg=GQ_AGG_I32, seed=0, rng_bits=32):
     return gq_params(int(scheme), int(s), int(pack), int(agg), int(rng_bits), 0, int(seed))
 
@@ -130,7 +165,8 @@ def norm_workspace_bytes(K, d):
 
 def global_norm(xs, kind, norm_out, status_flags=None, workspace=None, stream=None):
     """gq_global_norm over the K tensors xs (fp32, equal length).  Returns the workspace used."""
-    K, d = len(xs), (xs[0].numel() if xs else 0)
+    K, d = len(xs), _need_grads(xs)
+    _need(norm_out, 4, "norm_out"); _need(status_flags, 4, "status_flags")
     if workspace is None:
         workspace = torch.empty(max(norm_workspace_bytes(K, d), 8), dtype=torch.uint8, device=norm_out.device)
     st = _lib.gq_global_norm(_ptr_array(xs), K, d, int(kind), _ptr(norm_out), _ptr(status_flags),
@@ -140,25 +176,33 @@ def global_norm(xs, kind, norm_out, status_flags=None, workspace=None, stream=No
 
 
 def quantize(x, norm, params, worker, index_base, levels_out, signplane_out=None, stream=None):
+    d = _need_grads([x])
+    _need(norm, 4, "norm")
+    _need_levels([levels_out], [signplane_out] if signplane_out is not None else None, d, params, "levels_out")
     st = _lib.gq_quantize(_ptr(x), x.numel(), _ptr(norm), C.byref(params), int(worker), int(index_base),
                           _ptr(levels_out), _ptr(signplane_out), _stream(stream))
     _check(st, "gq_quantize")
 
 
 def int_aggregate(levels, signplanes, d, params, agg_out, stream=None):
+    _need_levels(levels, signplanes, int(d), params)
+    _need(agg_out, _agg_bytes(params) * int(d), "agg_out")
     st = _lib.gq_int_aggregate(_ptr_array(levels), _ptr_array(signplanes), len(levels), int(d),
                                C.byref(params), _ptr(agg_out), _stream(stream))
     _check(st, "gq_int_aggregate")
 
 
 def dequantize(agg, d, norm, params, K, out, stream=None):
+    _need(agg, _agg_bytes(params) * int(d), "agg"); _need(out, 4 * int(d), "out"); _need(norm, 4, "norm")
     st = _lib.gq_dequantize(_ptr(agg), int(d), _ptr(norm), C.byref(params), int(K), _ptr(out), _stream(stream))
     _check(st, "gq_dequantize")
 
 
 def fused_quantize_aggregate(xs, norm, params, index_base=0, agg_out=None, dequant_out=None,
                              levels_out=None, signplanes_out=None, stream=None):
-    K, d = len(xs), (xs[0].numel() if xs else 0)
+    K, d = len(xs), _need_grads(xs)
+    _need(norm, 4, "norm"); _need(agg_out, _agg_bytes(params) * d, "agg_out"); _need(dequant_out, 4 * d, "dequant_out")
+    _need_levels(levels_out, signplanes_out, d, params, "levels_out")
     st = _lib.gq_fused_quantize_aggregate(_ptr_array(xs), K, d, _ptr(norm), C.byref(params), int(index_base),
                                           _ptr(agg_out), _ptr(dequant_out), _ptr_array(levels_out),
                                           _ptr_array(signplanes_out), _stream(stream))
@@ -166,12 +210,18 @@ def fused_quantize_aggregate(xs, norm, params, index_base=0, agg_out=None, dequa
 
 
 def exp_reduce(levels, d, params, index_base=0, norm=None, reduced_out=None, dequant_out=None, stream=None):
+    for t in levels:
+        _need(t, int(d), "levels")                               # int8 codes
+    _need(reduced_out, int(d), "reduced_out"); _need(dequant_out, 4 * int(d), "dequant_out"); _need(norm, 4, "norm")
     st = _lib.gq_exp_reduce(_ptr_array(levels), len(levels), int(d), C.byref(params), int(index_base), _ptr(norm),
                             _ptr(reduced_out), _ptr(dequant_out), _stream(stream))
     _check(st, "gq_exp_reduce")
 
 
 def avg_reduce(levels, d, params, index_base=0, norm=None, reduced_out=None, dequant_out=None, stream=None):
+    _need_levels(levels, None, int(d), params)
+    _need(reduced_out, levels_nbytes(int(d), params.pack), "reduced_out"); _need(dequant_out, 4 * int(d), "dequant_out")
+    _need(norm, 4, "norm")
     st = _lib.gq_avg_reduce(_ptr_array(levels), len(levels), int(d), C.byref(params), int(index_base), _ptr(norm),
                             _ptr(reduced_out), _ptr(dequant_out), _stream(stream))
     _check(st, "gq_avg_reduce")
@@ -183,6 +233,8 @@ def compact_workspace_bytes(d):
 
 def compact(levels, d, params, indices_out, values_out, count_out, workspace=None, stream=None):
     """gq_compact: the non-zero int8 codes of one worker as (index, code) pairs.  Returns the workspace used."""
+    _need(levels, int(d), "levels"); _need(count_out, 8, "count_out")
+    _need(values_out, indices_out.numel(), "values_out"); _need(indices_out, 0, "indices_out")
     if workspace is None:
         workspace = torch.empty(max(compact_workspace_bytes(d), 4), dtype=torch.uint8, device=count_out.device)
     st = _lib.gq_compact(_ptr(levels), int(d), C.byref(params), _ptr(indices_out), _ptr(values_out),
@@ -193,6 +245,9 @@ def compact(levels, d, params, indices_out, values_out, count_out, workspace=Non
 
 
 def sparse_aggregate(indices, values, counts, d, params, agg_out, stream=None):
+    for i, v, c in zip(indices, values, counts):
+        _need(i, 0, "indices"); _need(v, i.numel(), "values"); _need(c, 8, "count")
+    _need(agg_out, 4 * int(d), "agg_out")
     caps = (C.c_int64 * len(indices))(*[t.numel() for t in indices])
     st = _lib.gq_sparse_aggregate(_ptr_array(indices), _ptr_array(values), _ptr_array(counts), caps, len(indices),
                                   int(d), C.byref(params), _ptr(agg_out), _stream(stream))

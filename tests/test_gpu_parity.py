@@ -166,6 +166,41 @@ def test_quantize_special_norms_and_values():
     assert np.array_equal(host(lv)[:d].view(np.int8), q.astype(np.int8)) and 0.4 < q.mean() < 0.6
 
 
+def test_binding_refuses_buffers_that_are_too_small():
+    # the C ABI cannot see sizes; the binding checks them before anything is launched
+    d = 4096
+    xs = gaussians(2, d, seed=4)
+    n = dev_scalar(1.0)
+    P = gq.make_params
+    ok_lv = torch.zeros(d, dtype=torch.uint8, device=DEV)
+    ok_agg = torch.zeros(d, dtype=torch.int32, device=DEV)
+    with pytest.raises(ValueError):
+        gq.quantize(xs[0], n, P(0, 127), 0, 0, ok_lv[:d - 1])
+    with pytest.raises(ValueError):
+        gq.quantize(xs[0], n, P(0, 15, gq.GQ_PACK_U4_SIGNPLANE), 0, 0, ok_lv, torch.zeros(d // 32 - 1, dtype=torch.int32, device=DEV))
+    with pytest.raises(ValueError):
+        gq.quantize(xs[0].double(), n, P(0, 127), 0, 0, ok_lv)
+    with pytest.raises(ValueError):
+        gq.quantize(xs[0][::2], n, P(0, 127), 0, 0, ok_lv)                       # not contiguous
+    with pytest.raises(ValueError):
+        gq.fused_quantize_aggregate(xs, n, P(0, 127), 0, ok_agg[:d - 1])
+    with pytest.raises(ValueError):
+        gq.fused_quantize_aggregate([xs[0], xs[1][:d - 4]], n, P(0, 127), 0, ok_agg)
+    with pytest.raises(ValueError):
+        gq.fused_quantize_aggregate(xs, n, P(0, 127), 0, ok_agg, None, [ok_lv, ok_lv[:100]])
+    with pytest.raises(ValueError):
+        gq.int_aggregate([ok_lv, ok_lv], None, d, P(0, 127), ok_agg.short())       # int32 sum into 2-byte elements
+    with pytest.raises(ValueError):
+        gq.dequantize(ok_agg, d, n, P(0, 127), 2, torch.zeros(d - 1, device=DEV))
+    with pytest.raises(ValueError):
+        gq.global_norm(xs, 0, n.cpu())
+    with pytest.raises(ValueError):
+        gq.exp_reduce([ok_lv, ok_lv[:7]], d, P(1, 7), 0, n, ok_lv, None)
+    # int16 sums need only two bytes per coordinate
+    gq.fused_quantize_aggregate(xs, n, P(0, 127, 0, gq.GQ_AGG_I16), 0, torch.zeros(d, dtype=torch.int16, device=DEV))
+    torch.cuda.synchronize()
+
+
 def test_argument_errors():
     d = 1024
     x = gaussians(1, d + 4, seed=3)[0]
@@ -236,8 +271,8 @@ def check_int_aggregate(scheme, s, pack, agg, K, d):
     if gq.check_width(params, K) != gq.GQ_OK:
         assert not O.check_width(SCHEMES[scheme], s, K, 16 if agg else 32)
         with pytest.raises(gq.GQError):
-            gq.int_aggregate([torch.zeros(16, dtype=torch.uint8, device=DEV)] * K, None, d, params,
-                             torch.zeros(16, dtype=torch.int32, device=DEV))
+            gq.int_aggregate([torch.zeros(d + 16, dtype=torch.uint8, device=DEV)] * K, None, d, params,
+                             torch.zeros(d + 16, dtype=torch.int32, device=DEV))
         return
     assert O.check_width(SCHEMES[scheme], s, K, 16 if agg else 32) and O.fits_width(want, 16 if agg else 32)
     lvs, sps = [], []
@@ -614,8 +649,9 @@ def test_compact_errors():
     with pytest.raises(gq.GQError) as e:
         gq.compact(lv, 64, gq.make_params(0, 7, PACKS["i4"]), idx, val, cnt)
     assert e.value.status == gq.GQ_ERR_UNSUPPORTED
+    big = torch.zeros(1 << 20, dtype=torch.int8, device=DEV)
     with pytest.raises(gq.GQError) as e:
-        gq.compact(lv, 1 << 20, gq.make_params(0, 127), idx, val, cnt, workspace=torch.zeros(8, dtype=torch.uint8, device=DEV))
+        gq.compact(big, 1 << 20, gq.make_params(0, 127), idx, val, cnt, workspace=torch.zeros(8, dtype=torch.uint8, device=DEV))
     assert e.value.status == gq.GQ_ERR_WORKSPACE
     assert gq.compact_workspace_bytes(-1) == 0 and gq.compact_workspace_bytes(1 << 33) == 0
     assert gq.compact_workspace_bytes(0) == 4 and gq.compact_workspace_bytes(4097) == 8
