@@ -7,16 +7,11 @@
 #include "gq_device.hpp"
 #include "gq_host.hpp"
 
-namespace gq {
-
-
-}  // namespace gq
-
 using namespace gq;
 
 extern "C" {
 
-int gq_version(void) { return 1000; }
+int gq_version(void) { return 1001; }
 
 const char *gq_status_string(gq_status st)
 {
