@@ -16,25 +16,33 @@ namespace gq {
 // tree order; every node rounds its sum to a neighbouring power of two with the random integer
 // k, P(k > b) = 2^-b.  A lane owns four coordinates and walks the tree depth first with a stack of
 // log2(n') + 1 partial results, so the K code words are consumed as they arrive.
-// One signed int holds a pair: se = sign * e (0 for zero).
 // =============================================================================================
 constexpr int kReduceBlock = 128;
 
-__device__ __forceinline__ int alg2_pair(int se1, int se2, uint32_t r)
+// A partial result inside the kernel: sg carries the sign in its top bit (its other bits are free), e is
+// the exponent of 2^-e, and ZERO is stood for by any e >= kZeroE / 2.  With zero as a huge exponent the
+// listing's special cases for zero operands disappear: 2^-e + "2^-huge" never rounds away from 2^-e,
+// because the random integer k is at most 33.
+constexpr int kZeroE = 1 << 20;
+struct Pow2 { int sg; int e; };
+
+// One node of Algorithm 2: the sum of two signed powers of two, rounded to a neighbouring power of two.
+// a = the operand with the smaller exponent (operand 1 on a tie), diff = e_b - e_a.
+//   same signs      2^-ea + 2^-eb lies in [2^-ea, 2^-(ea-1)]: up to 2^-(ea-1) iff k > diff
+//   opposite signs  2^-ea - 2^-eb lies in [2^-(ea+1), 2^-ea]: down to 2^-(ea+1) iff k > diff - 1; 0 if diff = 0
+// with k = 1 + (leading zeros of r), so k > t iff clz(r) >= t.
+__device__ __forceinline__ Pow2 alg2_pair(const Pow2 &x1, const Pow2 &x2, uint32_t r)
 {
-    const int k = __clz((int)r) + 1;                       // P(k > b) = 2^-b; 33 for r = 0
-    const int e1 = abs(se1), e2 = abs(se2);
-    const bool both = (e1 > 0) && (e2 > 0);
-    const bool opposite = both && ((se1 ^ se2) < 0);        // sign12 = -1
-    const bool same = both && ((se1 ^ se2) >= 0);           // sign12 = +1
-    const int diff = abs(e1 - e2) - (opposite ? 1 : 0);
-    const bool smaller = (e1 > 0) && (e1 <= e2 || e2 == 0); // operand 1 has the larger magnitude
-    const bool nonzero = !(opposite && e1 == e2);
-    const int sel = smaller ? se1 : se2;
-    const int e_sel = smaller ? e1 : e2;
-    const int adj = (k > diff) ? (same ? -1 : (opposite ? 1 : 0)) : 0;
-    const int e = nonzero ? e_sel + adj : 0;
-    return sel < 0 ? -e : e;
+    const int lead = __clz((int)r);                                  // leading zeros of r, 32 for r = 0
+    const bool first = x1.e <= x2.e;
+    const int ea = min(x1.e, x2.e), eb = max(x1.e, x2.e);
+    const int opp = (int)((uint32_t)(x1.sg ^ x2.sg) >> 31);          // 1 iff the signs differ
+    const int t = (eb - ea) - opp;                                   // -1: equal magnitudes, opposite signs
+    const int step = (lead >= t) ? (opp ? 1 : -1) : 0;
+    Pow2 o;
+    o.sg = first ? x1.sg : x2.sg;
+    o.e = t < 0 ? kZeroE : ea + step;
+    return o;
 }
 
 template <int NPAD, bool UNIFORM_HI>
@@ -65,13 +73,15 @@ exp_reduce_kernel(LevelCPtrs Lv, int K, int64_t d, int s, uint64_t seed, uint64_
         for (int i = 0; i < nvalid; i++) t |= (uint32_t)b[i] << (8 * i);
         return t;
     };
-    // code k >= 1 of the exponential grid -> e = s - k + 1 + L; 0 stays 0
-    auto leaf = [&](uint32_t word, int i) -> int {
+    // code k >= 1 of the exponential grid -> e = s - k + 1 + L; code 0 is zero
+    auto leaf = [&](uint32_t word, int i) -> Pow2 {
         const int q = (int)(int8_t)(word >> (8 * i));
-        const int e = q ? s + 1 + L - abs(q) : 0;
-        return q < 0 ? -e : e;
+        Pow2 x;
+        x.sg = q;
+        x.e = q ? s + 1 + L - abs(q) : kZeroE;
+        return x;
     };
-    int st[L + 1][4];                                       // the stack of partial results
+    int st_sg[L + 1][4], st_e[L + 1][4];                    // the stack of partial results (sign carrier, exponent)
     constexpr int kBatch = NPAD < 8 ? NPAD : 8;
 #pragma unroll
     for (int w0 = 0; w0 < NPAD; w0 += kBatch) {
@@ -83,22 +93,31 @@ exp_reduce_kernel(LevelCPtrs Lv, int K, int64_t d, int s, uint64_t seed, uint64_
             const int i = w0 + j;                            // leaf index; the stack depth is popcount(i)
             int top = __builtin_popcount((unsigned)i);
 #pragma unroll
-            for (int c = 0; c < 4; c++) st[top][c] = leaf(words[j], c);
+            for (int c = 0; c < 4; c++) { const Pow2 x = leaf(words[j], c); st_sg[top][c] = x.sg; st_e[top][c] = x.e; }
 #pragma unroll
             for (int lvl = 1; lvl <= L; lvl++) {
                 if (((i + 1) & ((1 << lvl) - 1)) == 0) {     // a subtree of 2^lvl leaves is complete
                     const uint32_t node = (uint32_t)((NPAD >> lvl) + (i >> lvl));   // heap numbering
                     const Words4 r = philox4x32_10(c_lo, c_hi, node, 1u, k0, k1);
 #pragma unroll
-                    for (int c = 0; c < 4; c++) st[top - 1][c] = alg2_pair(st[top - 1][c], st[top][c], r.w[c]);
+                    for (int c = 0; c < 4; c++) {
+                        const Pow2 o = alg2_pair(Pow2{st_sg[top - 1][c], st_e[top - 1][c]}, Pow2{st_sg[top][c], st_e[top][c]}, r.w[c]);
+                        st_sg[top - 1][c] = o.sg; st_e[top - 1][c] = o.e;
+                    }
                     top--;
                 }
             }
         }
     }
+    int root[4];                                            // sign * e of the root, 0 for zero
+#pragma unroll
+    for (int c = 0; c < 4; c++) {
+        const int e = st_e[0][c] >= kZeroE / 2 ? 0 : st_e[0][c];
+        root[c] = st_sg[0][c] < 0 ? -e : e;
+    }
     if (reduced_out) {
-        const uint32_t wout = (uint32_t)(st[0][0] & 255) | ((uint32_t)(st[0][1] & 255) << 8) |
-                              ((uint32_t)(st[0][2] & 255) << 16) | ((uint32_t)(st[0][3] & 255) << 24);
+        const uint32_t wout = (uint32_t)(root[0] & 255) | ((uint32_t)(root[1] & 255) << 8) |
+                              ((uint32_t)(root[2] & 255) << 16) | ((uint32_t)(root[3] & 255) << 24);
         if (nvalid == 4) {
             __builtin_nontemporal_store(wout, reinterpret_cast<uint32_t *>(reduced_out) + v);
         } else {
@@ -113,7 +132,7 @@ exp_reduce_kernel(LevelCPtrs Lv, int K, int64_t d, int s, uint64_t seed, uint64_
         float o[4];
 #pragma unroll
         for (int i = 0; i < 4; i++) {
-            const int se = st[0][i], e = abs(se);
+            const int se = root[i], e = abs(se);
             const float p2 = __uint_as_float((uint32_t)(127 + 1 + L - e) << 23);     // 2^(1+L-e), e <= s+L <= 37
             o[i] = e ? (se < 0 ? -(c * p2) : c * p2) : 0.0f;
         }
