@@ -43,6 +43,8 @@ def parse():
                     help="after the timed steps, run three plain 1 GiB device copies (a kernel of known "
                          "traffic for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="also capture the step in a HIP graph and time its replays (reported as graph_replay_ms_per_step)")
     return ap.parse_args()
 
 
@@ -279,6 +281,25 @@ def main():
                        "dequantize": (b_deq / float(np.mean(t_deq)) * 1e-6) if b_deq else None},
         "norm_flags": int(flags.item()),
     }
+    if args.graph:
+        # the calls only enqueue (no allocation, no synchronisation), so the step can be captured once and replayed:
+        # what a launch-bound caller (small d) gains from that
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                step()
+        torch.cuda.current_stream().wait_stream(side)
+        for _ in range(args.warmup):
+            g.replay()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(args.steps):
+            g.replay()
+        b.record(); b.synchronize()
+        line["graph_replay_ms_per_step"] = a.elapsed_time(b) / args.steps
     if args.rows:
         line["rows"] = time_rows(gq, torch, xs, norm, params, cfg, args)
     if args.calibration_copy:
