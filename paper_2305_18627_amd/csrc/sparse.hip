@@ -17,7 +17,9 @@ namespace gq {
 // the K sorted lists are merged tile by tile into the dense int32 sum.
 // =============================================================================================
 constexpr int kCompactBlock = 256;
-constexpr int kCompactTile = kCompactBlock * 16;        // codes per block: one 128-bit load per thread
+constexpr int kCompactTile = kCompactBlock * 16;        // codes per tile: one 128-bit load per thread
+constexpr int kCompactTiles = 4;                        // consecutive tiles per block: fewer, larger block counts to scan
+constexpr int kCompactSpan = kCompactTile * kCompactTiles;
 constexpr int kScanBlock = 1024;
 
 __device__ __forceinline__ uint32_t nonzero_bytes(uint32_t x)    // 0x80 in every byte of x that is not zero
@@ -69,10 +71,15 @@ __global__ void __launch_bounds__(kCompactBlock)
 compact_count_kernel(const uint8_t *__restrict__ lv, int64_t d, uint32_t *__restrict__ block_counts)
 {
     __shared__ uint32_t sh[kCompactBlock / 64];
-    const int64_t t = (int64_t)blockIdx.x * kCompactBlock + threadIdx.x;
-    const uint32_t c = count_unit(load_code_unit(lv, t, d));
+    const int64_t t0 = (int64_t)blockIdx.x * (kCompactBlock * kCompactTiles) + threadIdx.x;
+    u32x4 c[kCompactTiles];
+#pragma unroll
+    for (int j = 0; j < kCompactTiles; j++) c[j] = load_code_unit(lv, t0 + (int64_t)j * kCompactBlock, d);
+    uint32_t mine = 0;
+#pragma unroll
+    for (int j = 0; j < kCompactTiles; j++) mine += count_unit(c[j]);
     uint32_t total;
-    block_exclusive_scan<kCompactBlock>(c, sh, &total);
+    block_exclusive_scan<kCompactBlock>(mine, sh, &total);
     if (threadIdx.x == 0) block_counts[blockIdx.x] = total;
 }
 
@@ -95,8 +102,9 @@ compact_scan_kernel(uint32_t *__restrict__ counts, int64_t n, uint64_t *__restri
     if (threadIdx.x == 0) *total_out = (uint64_t)carry;
 }
 
-// The block's pairs are first ranked into LDS (a block never holds more than kCompactTile of them) and then
-// copied out with consecutive lanes writing consecutive list entries.
+// A block takes its kCompactTiles tiles one after the other.  The pairs of a tile are first ranked into LDS (a
+// tile never holds more than kCompactTile of them) and then copied out with consecutive lanes writing
+// consecutive list entries; the list position runs on from tile to tile.
 __global__ void __launch_bounds__(kCompactBlock)
 compact_write_kernel(const uint8_t *__restrict__ lv, int64_t d, const uint32_t *__restrict__ block_offsets,
                      uint32_t *__restrict__ indices_out, int8_t *__restrict__ values_out, int64_t capacity)
@@ -104,27 +112,35 @@ compact_write_kernel(const uint8_t *__restrict__ lv, int64_t d, const uint32_t *
     __shared__ uint32_t sh[kCompactBlock / 64];
     __shared__ uint32_t s_idx[kCompactTile];
     __shared__ int8_t s_val[kCompactTile];
-    const int64_t t = (int64_t)blockIdx.x * kCompactBlock + threadIdx.x;
-    const u32x4 c = load_code_unit(lv, t, d);
-    uint32_t total;
-    uint32_t rank = block_exclusive_scan<kCompactBlock>(count_unit(c), sh, &total);
-    const uint32_t w[4] = {c.x, c.y, c.z, c.w};
+    const int64_t t0 = (int64_t)blockIdx.x * (kCompactBlock * kCompactTiles) + threadIdx.x;
+    u32x4 c[kCompactTiles];
 #pragma unroll
-    for (int i = 0; i < 16; i++) {
-        const uint32_t b = (w[i >> 2] >> (8 * (i & 3))) & 255u;
-        if (b != 0u) {
-            s_idx[rank] = (uint32_t)((t << 4) + i);
-            s_val[rank] = (int8_t)b;
-            rank++;
+    for (int j = 0; j < kCompactTiles; j++) c[j] = load_code_unit(lv, t0 + (int64_t)j * kCompactBlock, d);
+    int64_t base = (int64_t)block_offsets[blockIdx.x];
+#pragma unroll
+    for (int j = 0; j < kCompactTiles; j++) {
+        const int64_t t = t0 + (int64_t)j * kCompactBlock;
+        uint32_t total;
+        uint32_t rank = block_exclusive_scan<kCompactBlock>(count_unit(c[j]), sh, &total);
+        const uint32_t w[4] = {c[j].x, c[j].y, c[j].z, c[j].w};
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            const uint32_t b = (w[i >> 2] >> (8 * (i & 3))) & 255u;
+            if (b != 0u) {
+                s_idx[rank] = (uint32_t)((t << 4) + i);
+                s_val[rank] = (int8_t)b;
+                rank++;
+            }
         }
-    }
-    __syncthreads();
-    const int64_t base = (int64_t)block_offsets[blockIdx.x];
-    for (uint32_t e = threadIdx.x; e < total; e += kCompactBlock) {
-        if (base + e < capacity) {
-            indices_out[base + e] = s_idx[e];
-            values_out[base + e] = s_val[e];
+        __syncthreads();
+        for (uint32_t e = threadIdx.x; e < total; e += kCompactBlock) {
+            if (base + e < capacity) {
+                indices_out[base + e] = s_idx[e];
+                values_out[base + e] = s_val[e];
+            }
         }
+        base += total;
+        __syncthreads();                                 // the staging area is reused by the next tile
     }
 }
 
@@ -196,7 +212,7 @@ extern "C" {
 size_t gq_compact_workspace_bytes(int64_t d)
 {
     if (d < 0 || d > 0xFFFFFFFFLL) return 0;
-    const int64_t blocks = (d + kCompactTile - 1) / kCompactTile;
+    const int64_t blocks = (d + kCompactSpan - 1) / kCompactSpan;
     return (size_t)(blocks > 0 ? blocks : 1) * sizeof(uint32_t);
 }
 
@@ -214,7 +230,7 @@ gq_status gq_compact(const void *levels, int64_t d, const gq_params *p, uint32_t
     if (!aligned(workspace, 4)) return GQ_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)hip_stream;
     uint32_t *counts = reinterpret_cast<uint32_t *>(workspace);
-    const int64_t blocks = (d + kCompactTile - 1) / kCompactTile;
+    const int64_t blocks = (d + kCompactSpan - 1) / kCompactSpan;
     if (!grid_fits(blocks)) return GQ_ERR_INVALID_ARG;
     const uint8_t *lv = reinterpret_cast<const uint8_t *>(levels);
     if (blocks > 0) {
