@@ -151,55 +151,78 @@ struct SparseLists {
     int64_t cap[kMaxWorkers];
 };
 
-// Receiver side.  A block owns a tile of kSparseTile coordinates: two threads per worker find, by binary
-// search in the sorted index list, the entries that fall into the tile; the block adds their integer
-// values into an LDS copy of the tile (LDS atomics) and writes the tile with 128-bit stores.  No global
-// atomics and no separate zero fill: every output word is written exactly once.
+// Receiver side.  A block owns kSparseTiles consecutive tiles of kSparseTile coordinates.  It first finds, by
+// binary search in every worker's sorted index list, where each of its tile boundaries falls (all
+// K * (kSparseTiles + 1) searches run side by side, one per thread, so the block pays the latency of one
+// search).  Then, tile by tile, the workers' entries are added into an LDS copy of the tile (LDS atomics), the
+// threads being split evenly over the workers so that short lists are walked in parallel, and the tile is
+// written with 128-bit stores.  No global atomics and no separate zero fill: every output word is written
+// exactly once.
 constexpr int kSparseTile = 4096;
+constexpr int kSparseTiles = 4;
 
 template <int SCHEME>
-__global__ void __launch_bounds__(kBlock) sparse_tile_kernel(SparseLists S, int K, int64_t d, int *__restrict__ agg)
+__global__ void __launch_bounds__(kBlock)
+sparse_tile_kernel(SparseLists S, int K, int lanes_per_worker, int64_t d, int *__restrict__ agg)
 {
     __shared__ int tile[kSparseTile];
-    __shared__ int64_t range[2 * kMaxWorkers];
-    const int64_t lo = (int64_t)blockIdx.x * kSparseTile;
-    const int64_t hi = lo + kSparseTile < d ? lo + kSparseTile : d;
-    for (int i = threadIdx.x; i < kSparseTile; i += kBlock) tile[i] = 0;
-    if ((int)threadIdx.x < 2 * K) {
-        const int w = threadIdx.x >> 1;
-        const int64_t key = (threadIdx.x & 1) ? hi : lo;
+    __shared__ int64_t bound[kMaxWorkers * (kSparseTiles + 1)];
+    const int64_t lo0 = (int64_t)blockIdx.x * (kSparseTile * kSparseTiles);
+    for (int b = threadIdx.x; b < K * (kSparseTiles + 1); b += kBlock) {
+        const int w = b / (kSparseTiles + 1), t = b - w * (kSparseTiles + 1);
+        const int64_t edge = lo0 + (int64_t)t * kSparseTile;
+        const int64_t key = edge < d ? edge : d;
         const uint64_t have = *S.cnt[w];
         const int64_t n = have < (uint64_t)S.cap[w] ? (int64_t)have : S.cap[w];
-        int64_t a = 0, b = n;                                  // first entry whose index is >= key
-        while (a < b) {
-            const int64_t mid = (a + b) >> 1;
-            if ((int64_t)S.idx[w][mid] < key) a = mid + 1; else b = mid;
+        int64_t a = 0, e = n;                                  // first entry whose index is >= key
+        while (a < e) {
+            const int64_t mid = (a + e) >> 1;
+            if ((int64_t)S.idx[w][mid] < key) a = mid + 1; else e = mid;
         }
-        range[threadIdx.x] = a;
+        bound[b] = a;
     }
-    __syncthreads();
-    for (int w = 0; w < K; w++) {
-        const int64_t end = range[2 * w + 1];
-        for (int64_t e = range[2 * w] + threadIdx.x; e < end; e += kBlock) {
-            const int64_t j = (int64_t)S.idx[w][e] - lo;
-            const int q = S.val[w][e];
+    const int w = (int)threadIdx.x / lanes_per_worker;         // this thread's worker (if w < K) and its slot
+    const int slot = (int)threadIdx.x - w * lanes_per_worker;
+#pragma unroll 1
+    for (int t = 0; t < kSparseTiles; t++) {
+        const int64_t lo = lo0 + (int64_t)t * kSparseTile;
+        if (lo >= d) break;                                     // uniform over the block
+        for (int i = threadIdx.x; i < kSparseTile; i += kBlock) tile[i] = 0;
+        __syncthreads();                                        // also orders the searches before their first use
+        auto add_entry = [&](int ww, int64_t e) {
+            const int64_t j = (int64_t)S.idx[ww][e] - lo;
+            const int q = S.val[ww][e];
             int val = q;
             if (SCHEME == 1) {
                 const int mag = (int)((1u << abs(q)) >> 1);
                 val = q < 0 ? -mag : mag;
             }
             if (j >= 0 && j < kSparseTile) atomicAdd(&tile[j], val);   // always true for a sorted list
+        };
+        // long lists: the whole block walks one worker's entries at a time (1 KiB contiguous per wave and load);
+        // short lists: the threads are split over the workers, which are then walked side by side
+        int64_t entries = 0;
+        for (int ww = 0; ww < K; ww++) entries += bound[ww * (kSparseTiles + 1) + t + 1] - bound[ww * (kSparseTiles + 1) + t];
+        if (entries >= (int64_t)K * (kBlock / 2)) {             // uniform over the block
+            for (int ww = 0; ww < K; ww++) {
+                const int64_t end = bound[ww * (kSparseTiles + 1) + t + 1];
+                for (int64_t e = bound[ww * (kSparseTiles + 1) + t] + threadIdx.x; e < end; e += kBlock) add_entry(ww, e);
+            }
+        } else if (w < K) {
+            const int64_t end = bound[w * (kSparseTiles + 1) + t + 1];
+            for (int64_t e = bound[w * (kSparseTiles + 1) + t] + slot; e < end; e += lanes_per_worker) add_entry(w, e);
         }
-    }
-    __syncthreads();
-    for (int i = threadIdx.x * 4; i < kSparseTile; i += kBlock * 4) {
-        const int64_t c = lo + i;
-        if (c + 4 <= d) {
-            const i32x4 o = {tile[i], tile[i + 1], tile[i + 2], tile[i + 3]};
-            __builtin_nontemporal_store(o, reinterpret_cast<i32x4 *>(agg + c));
-        } else {
-            for (int t = 0; t < 4 && c + t < d; t++) agg[c + t] = tile[i + t];
+        __syncthreads();
+        for (int i = threadIdx.x * 4; i < kSparseTile; i += kBlock * 4) {
+            const int64_t c = lo + i;
+            if (c + 4 <= d) {
+                const i32x4 o = {tile[i], tile[i + 1], tile[i + 2], tile[i + 3]};
+                __builtin_nontemporal_store(o, reinterpret_cast<i32x4 *>(agg + c));
+            } else {
+                for (int u = 0; u < 4 && c + u < d; u++) agg[c + u] = tile[i + u];
+            }
         }
+        __syncthreads();                                        // the tile is cleared again by the next round
     }
 }
 
@@ -270,11 +293,15 @@ gq_status gq_sparse_aggregate(const uint32_t *const *indices, const int8_t *cons
     if (d > 0 && !aligned(agg_out, 16)) return GQ_ERR_INVALID_ARG;
     if (d == 0) return GQ_OK;
     hipStream_t s = (hipStream_t)hip_stream;
-    const int64_t blocks = (d + kSparseTile - 1) / kSparseTile;
+    const int64_t span = (int64_t)kSparseTile * kSparseTiles;
+    const int64_t blocks = (d + span - 1) / span;
     if (!grid_fits(blocks)) return GQ_ERR_INVALID_ARG;
     const dim3 grid((unsigned)blocks);
-    if (p->scheme == GQ_LINEAR) hipLaunchKernelGGL(sparse_tile_kernel<0>, grid, dim3(kBlock), 0, s, S, K, d, (int *)agg_out);
-    else hipLaunchKernelGGL(sparse_tile_kernel<1>, grid, dim3(kBlock), 0, s, S, K, d, (int *)agg_out);
+    int kpad = 1;
+    while (kpad < K) kpad <<= 1;
+    const int lanes = kBlock / kpad;                            // threads per worker: 256 for K = 1 ... 4 for K = 64
+    if (p->scheme == GQ_LINEAR) hipLaunchKernelGGL(sparse_tile_kernel<0>, grid, dim3(kBlock), 0, s, S, K, lanes, d, (int *)agg_out);
+    else hipLaunchKernelGGL(sparse_tile_kernel<1>, grid, dim3(kBlock), 0, s, S, K, lanes, d, (int *)agg_out);
     if (launched() != GQ_OK) return GQ_ERR_DEVICE;
     return GQ_OK;
 }
