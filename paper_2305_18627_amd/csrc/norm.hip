@@ -136,17 +136,19 @@ __global__ void __launch_bounds__(kBlock) norm_partial_kernel(GradPtrs P, int64_
     const float *x = P.x[worker];
     const f32x4 *xv = reinterpret_cast<const f32x4 *>(x);
     const int64_t nvec = d >> 2;
-    const int64_t step = (int64_t)bpw * kBlock;
-    int64_t v = (int64_t)blk * kBlock + threadIdx.x;
+    // block `blk` of a worker takes a contiguous stretch of its vectors, eight 128-bit loads in flight per lane
+    const int64_t per_block = (((nvec + bpw - 1) / bpw) + kBlock - 1) / kBlock * kBlock;
+    const int64_t end = (blk + 1) * per_block < nvec ? (blk + 1) * per_block : nvec;
+    int64_t v = (int64_t)blk * per_block + threadIdx.x;
     NormAcc<MAXNORM> acc;
-    for (; v + 3 * step < nvec; v += 4 * step) {
-        const f32x4 b0 = __builtin_nontemporal_load(xv + v);
-        const f32x4 b1 = __builtin_nontemporal_load(xv + v + step);
-        const f32x4 b2 = __builtin_nontemporal_load(xv + v + 2 * step);
-        const f32x4 b3 = __builtin_nontemporal_load(xv + v + 3 * step);
-        acc.take(b0); acc.take(b1); acc.take(b2); acc.take(b3);
+    for (; v + 7 * kBlock < end; v += 8 * kBlock) {
+        f32x4 b[8];
+#pragma unroll
+        for (int j = 0; j < 8; j++) b[j] = __builtin_nontemporal_load(xv + v + j * kBlock);
+#pragma unroll
+        for (int j = 0; j < 8; j++) acc.take(b[j]);
     }
-    for (; v < nvec; v += step) acc.take(__builtin_nontemporal_load(xv + v));
+    for (; v < end; v += kBlock) acc.take(__builtin_nontemporal_load(xv + v));
     if (blk == 0 && (int64_t)threadIdx.x < (d & 3)) {            // ragged tail: up to three coordinates
         const f32x4 a = {x[(nvec << 2) + threadIdx.x], 0.0f, 0.0f, 0.0f};
         acc.take(a);
