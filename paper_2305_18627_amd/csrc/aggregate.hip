@@ -293,7 +293,7 @@ gq_status gq_int_aggregate(const void *const *levels, const uint32_t *const *sig
     const bool nibble_lut = p->pack == GQ_PACK_I4 || (p->pack == GQ_PACK_U4_SIGNPLANE && p->scheme == GQ_LINEAR);
     if (nibble_lut) {
         const int64_t wide_blocks = d / (kNibBlock * kNibCoords);
-        if (!grid_fits(wide_blocks)) return GQ_ERR_INVALID_ARG;
+        if (!grid_fits(wide_blocks, kNibBlock)) return GQ_ERR_INVALID_ARG;
         if (wide_blocks > 0) {
             const dim3 wgrid((unsigned)wide_blocks), wblock(kNibBlock);
             if (p->pack == GQ_PACK_U4_SIGNPLANE) hipLaunchKernelGGL((int_aggregate_nibble_kernel<0, true>), wgrid, wblock, 0, s, L, K, agg_out, p->agg);
@@ -305,7 +305,7 @@ gq_status gq_int_aggregate(const void *const *levels, const uint32_t *const *sig
         }
     }
     const int64_t blocks = (nvec - v_begin + kAggBlock - 1) / kAggBlock;
-    if (!grid_fits(blocks)) return GQ_ERR_INVALID_ARG;
+    if (!grid_fits(blocks, kAggBlock)) return GQ_ERR_INVALID_ARG;
     const dim3 grid((unsigned)blocks), block(kAggBlock);
 #define GQ_AGG(SC, PK) hipLaunchKernelGGL((int_aggregate_kernel<SC, PK>), grid, block, 0, s, L, K, d, v_begin, agg_out, p->agg)
     if (p->scheme == GQ_LINEAR) {
@@ -337,7 +337,7 @@ gq_status gq_dequantize(const void *agg, int64_t d, const float *norm, const gq_
     if (d == 0) return GQ_OK;
     const int64_t nvec = (d + 3) / 4;
     const int64_t blocks = (nvec + kBlock - 1) / kBlock;
-    if (!grid_fits(blocks)) return GQ_ERR_INVALID_ARG;
+    if (!grid_fits(blocks, kBlock)) return GQ_ERR_INVALID_ARG;
     const dim3 grid((unsigned)blocks), block(kBlock);
     const float div = dequant_divisor(p, K);
     hipStream_t s = (hipStream_t)hip_stream;

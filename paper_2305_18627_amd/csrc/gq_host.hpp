@@ -47,6 +47,7 @@ static inline gq_status launched()
     return hipGetLastError() == hipSuccess ? GQ_OK : GQ_ERR_DEVICE;
 }
 
-static inline bool grid_fits(int64_t blocks) { return blocks >= 0 && blocks <= 0x7FFFFFFF; }
+// A launch may hold at most 2^32 - 1 threads in x (HIP's limit on gridDim.x * blockDim.x).
+static inline bool grid_fits(int64_t blocks, int threads) { return blocks >= 0 && blocks * (int64_t)threads <= 0xFFFFFFFFLL; }
 
 }  // namespace gq

@@ -172,14 +172,14 @@ quantize_aggregate_kernel(GradPtrs P, LevelPtrs L, int K, int64_t d, int64_t v0,
     const int64_t nfull = d >> 2;
     const int lane = (int)(threadIdx.x & 63u);
     int64_t v[NV];
-    uint32_t local_call;                         // call index of this lane relative to the launch's first
+    uint64_t local_call;                         // call index of this lane relative to the launch's first
     if (HALF) {
-        const uint32_t chunk = blockIdx.x * (kFusedBlock / 64) + (threadIdx.x >> 6);   // 128 vectors per wave
-        v[0] = v0 + (int64_t)chunk * 128 + lane;
+        const uint64_t chunk = (uint64_t)blockIdx.x * (kFusedBlock / 64) + (threadIdx.x >> 6);   // 128 vectors per wave
+        v[0] = v0 + (int64_t)(chunk * 128u) + lane;
         v[NV - 1] = v[0] + 64;
-        local_call = chunk * 64u + (uint32_t)(lane >> 1) + (uint32_t)(lane & 1) * 32u;
+        local_call = chunk * 64u + (uint64_t)(lane >> 1) + (uint64_t)(lane & 1) * 32u;
     } else {
-        local_call = blockIdx.x * kFusedBlock + threadIdx.x;
+        local_call = (uint64_t)blockIdx.x * kFusedBlock + threadIdx.x;
         v[0] = v0 + (int64_t)local_call;
     }
     int nvalid[NV];
@@ -195,9 +195,9 @@ quantize_aggregate_kernel(GradPtrs P, LevelPtrs L, int K, int64_t d, int64_t v0,
     uint32_t c_lo, c_hi;
     if (UNIFORM_HI) {
         c_hi = (uint32_t)(first >> 32);
-        c_lo = (uint32_t)first + local_call;                                      // no carry (host)
+        c_lo = (uint32_t)first + (uint32_t)local_call;                            // fits and no carry (host)
     } else {
-        const uint64_t call = first + (uint64_t)local_call;
+        const uint64_t call = first + local_call;
         c_lo = (uint32_t)call;
         c_hi = (uint32_t)(call >> 32);
     }
@@ -470,7 +470,7 @@ static gq_status launch_quantize_aggregate(const GradPtrs &P, const LevelPtrs &L
 #define GQ_LAUNCH(KT, LV, UH, WIN, V0, COUNT)                                                                  \
     do {                                                                                                      \
         const int64_t blocks_ = ((COUNT) + kFusedBlock * kLaneVecs - 1) / (kFusedBlock * kLaneVecs);          \
-        if (!grid_fits(blocks_)) return GQ_ERR_INVALID_ARG;                                                   \
+        if (!grid_fits(blocks_, kFusedBlock)) return GQ_ERR_INVALID_ARG;                                                   \
         hipLaunchKernelGGL((quantize_aggregate_kernel<SCHEME, KT, LV, UH, WIN, HALF>), dim3((unsigned)blocks_), block, 0, st, \
                            P, L, K, d, (int64_t)(V0), (int64_t)(V0) + (int64_t)(COUNT), norm, p->s, p->seed, worker0,  \
                            call_base, p->pack, agg_out, p->agg, deq_out, div, win_period, win_open);          \
@@ -499,13 +499,15 @@ static gq_status launch_quantize_aggregate(const GradPtrs &P, const LevelPtrs &L
         else             { if (win) GQ_LAUNCH_K(false, true, 0, nvec); else GQ_LAUNCH_K(false, false, 0, nvec); }
         return launched();
     }
+    constexpr int64_t kMaxLaunchVecs = (int64_t)1 << 31;
     // One launch per stretch of vectors whose Philox call index shares its high 32 bits (a second
     // stretch exists only if the bucket crosses a multiple of 2^34 coordinates).
     int64_t v0 = 0;
     while (v0 < nvec) {
         const uint64_t first = call_base + (uint64_t)v0;
         const uint64_t room = ((uint64_t)1 << 32) - (first & 0xFFFFFFFFull);
-        const int64_t count = (uint64_t)(nvec - v0) < room ? (nvec - v0) : (int64_t)room;
+        int64_t count = (uint64_t)(nvec - v0) < room ? (nvec - v0) : (int64_t)room;
+        if (count > kMaxLaunchVecs) count = kMaxLaunchVecs;       // and no launch beyond HIP's limit of 2^32 - 1 threads
         if (win) GQ_LAUNCH_K(true, true, v0, count);
         else GQ_LAUNCH_K(true, false, v0, count);
         if (launched() != GQ_OK) return GQ_ERR_DEVICE;
@@ -537,7 +539,7 @@ gq_status gq_quantize(const float *x, int64_t d, const float *norm, const gq_par
     const int64_t nvec = (d + 3) / 4;
     const int64_t per_block = (int64_t)kQuantBlock * kQuantVec;          // vectors per workgroup, either mode
     const int64_t blocks = (nvec + per_block - 1) / per_block;
-    if (!grid_fits(blocks)) return GQ_ERR_INVALID_ARG;
+    if (!grid_fits(blocks, kQuantBlock)) return GQ_ERR_INVALID_ARG;
     const dim3 grid((unsigned)blocks), block(kQuantBlock);
     const int lane_vecs = half ? 2 : 1;                                  // vectors per Philox call
     const uint64_t call_base = (uint64_t)index_base / (uint64_t)(4 * lane_vecs);

@@ -282,7 +282,7 @@ gq_status gq_exp_reduce(const void *const *levels, int K, int64_t d, const gq_pa
     if (d == 0) return GQ_OK;
     const int64_t nvec = (d + 3) / 4;
     const int64_t blocks = (nvec + kReduceBlock - 1) / kReduceBlock;
-    if (!grid_fits(blocks)) return GQ_ERR_INVALID_ARG;
+    if (!grid_fits(blocks, kReduceBlock)) return GQ_ERR_INVALID_ARG;
     const dim3 grid((unsigned)blocks), block(kReduceBlock);
     const uint64_t call_base = (uint64_t)index_base / 4u;
     const bool one_stretch = ((call_base & 0xFFFFFFFFull) + (uint64_t)(blocks * kReduceBlock)) <= ((uint64_t)1 << 32);
@@ -328,7 +328,7 @@ gq_status gq_avg_reduce(const void *const *levels, int K, int64_t d, const gq_pa
     if (d == 0) return GQ_OK;
     const int64_t nvec = (d + 3) / 4;
     const int64_t blocks = (nvec + kReduceBlock - 1) / kReduceBlock;
-    if (!grid_fits(blocks)) return GQ_ERR_INVALID_ARG;
+    if (!grid_fits(blocks, kReduceBlock)) return GQ_ERR_INVALID_ARG;
     const dim3 grid((unsigned)blocks), block(kReduceBlock);
     const uint64_t call_base = (uint64_t)index_base / 4u;
     const bool one_stretch = ((call_base & 0xFFFFFFFFull) + (uint64_t)(blocks * kReduceBlock)) <= ((uint64_t)1 << 32);

@@ -254,7 +254,7 @@ gq_status gq_compact(const void *levels, int64_t d, const gq_params *p, uint32_t
     hipStream_t s = (hipStream_t)hip_stream;
     uint32_t *counts = reinterpret_cast<uint32_t *>(workspace);
     const int64_t blocks = (d + kCompactSpan - 1) / kCompactSpan;
-    if (!grid_fits(blocks)) return GQ_ERR_INVALID_ARG;
+    if (!grid_fits(blocks, kCompactBlock)) return GQ_ERR_INVALID_ARG;
     const uint8_t *lv = reinterpret_cast<const uint8_t *>(levels);
     if (blocks > 0) {
         hipLaunchKernelGGL(compact_count_kernel, dim3((unsigned)blocks), dim3(kCompactBlock), 0, s, lv, d, counts);
@@ -295,7 +295,7 @@ gq_status gq_sparse_aggregate(const uint32_t *const *indices, const int8_t *cons
     hipStream_t s = (hipStream_t)hip_stream;
     const int64_t span = (int64_t)kSparseTile * kSparseTiles;
     const int64_t blocks = (d + span - 1) / span;
-    if (!grid_fits(blocks)) return GQ_ERR_INVALID_ARG;
+    if (!grid_fits(blocks, kBlock)) return GQ_ERR_INVALID_ARG;
     const dim3 grid((unsigned)blocks);
     int kpad = 1;
     while (kpad < K) kpad <<= 1;

@@ -133,6 +133,11 @@ def test_argument_checks_need_no_device(gq):
     assert lib.gq_int_aggregate(arr, None, 2, 16, C.byref(P(gq.GQ_LINEAR, 15, gq.GQ_PACK_U4_SIGNPLANE)), fake, None) == I
     assert lib.gq_int_aggregate(bad_arr, None, 2, 16, C.byref(ok), fake, None) == I
     assert lib.gq_int_aggregate(arr, None, 2, 16, C.byref(ok), odd, None) == I
+    # a launch holds at most 2^32 - 1 threads: sizes that one launch cannot cover are refused, not launched
+    assert lib.gq_int_aggregate(arr, None, 2, 1 << 34, C.byref(ok), fake, None) == I
+    assert lib.gq_dequantize(fake, 1 << 34, fake, C.byref(ok), 2, fake, None) == I
+    assert lib.gq_fused_quantize_aggregate(arr, 2, 1 << 34, fake, C.byref(ok), 0, fake, None, arr, None, None) == I
+    assert lib.gq_exp_reduce(arr, 2, 1 << 34, C.byref(P(gq.GQ_EXP, 7)), 0, fake, fake, None, None) == I
     assert lib.gq_dequantize(fake, 16, fake, C.byref(ok), 0, fake, None) == I
     assert lib.gq_dequantize(odd, 16, fake, C.byref(ok), 2, fake, None) == I
     assert lib.gq_exp_reduce(arr, 2, 16, C.byref(ok), 0, fake, fake, None, None) == gq.GQ_ERR_UNSUPPORTED   # not GQ_EXP

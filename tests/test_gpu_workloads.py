@@ -164,3 +164,41 @@ def test_workload_c5_bucketed_fused_quantize_aggregate_dequantize():
     expect = sum(float(x.double().sum()) for x in xs) / K
     sd = float(nf) / (K * s) * np.sqrt(K * d * 0.25)
     assert abs(tot - expect) <= 6.0 * sd
+
+
+def test_one_launch_across_two_to_the_34_coordinates():
+    # a single worker of 2^34 + 2^20 + 5 coordinates (69 GB): the Philox call index crosses 2^32 INSIDE the call, which
+    # the library handles by cutting the launch there; element indices pass 2^32 and byte offsets 2^36
+    torch.cuda.empty_cache()
+    d = (1 << 34) + (1 << 20) + 5
+    free, _ = torch.cuda.mem_get_info()
+    if free < 4 * d + 2 * d + (8 << 30):
+        pytest.skip("needs 110 GB of free device memory")
+    x = torch.empty(d, dtype=torch.float32, device=DEV)
+    g = torch.Generator(device=DEV).manual_seed(2034)
+    step = 1 << 28
+    for lo in range(0, d, step):
+        x[lo:lo + step].normal_(0.0, 1e-3, generator=g)
+    nf = np.float32(4.5e-3)
+    x.clamp_(-float(nf), float(nf))
+    norm_t = torch.tensor([float(nf)], device=DEV)
+    p = gq.make_params(gq.GQ_LINEAR, 127, gq.GQ_PACK_I8, gq.GQ_AGG_I16, seed=SI.QUANT_SEED)
+    agg = torch.empty(d, dtype=torch.int16, device=DEV)
+    gq.fused_quantize_aggregate([x], norm_t, p, 0, agg)
+    torch.cuda.synchronize()
+    edge = 1 << 34
+    for lo, hi in [(0, 1 << 16), (edge - (1 << 16), edge + (1 << 16)), (d - (1 << 16) - 5, d), (3 * (1 << 32) + 8, 3 * (1 << 32) + 8 + (1 << 15))]:
+        want = O.quantize_aggregate([host(x[lo:hi])], nf, O.LINEAR, 127, SI.QUANT_SEED, lo & ~3 if lo % 4 else lo)[0:hi - lo] \
+            if lo % 4 == 0 else None
+        if want is None:
+            lo4 = lo & ~3
+            want = O.quantize_aggregate([host(x[lo4:hi])], nf, O.LINEAR, 127, SI.QUANT_SEED, lo4)[lo - lo4:]
+        assert np.array_equal(host(agg[lo:hi]).astype(np.int64), want), lo
+    # the tail of the same gradient as a bucket with its offset
+    lo = edge - (1 << 20)
+    part = torch.empty(d - lo, dtype=torch.int16, device=DEV)
+    gq.fused_quantize_aggregate([x[lo:]], norm_t, p, lo, part)
+    torch.cuda.synchronize()
+    assert torch.equal(part, agg[lo:])
+    del x, agg, part
+    torch.cuda.empty_cache()
