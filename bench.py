@@ -152,7 +152,7 @@ def time_rows(gq, torch, xs, norm, params, cfg, args):
         red = torch.empty(gq.levels_nbytes(d, pack), dtype=torch.uint8, device=dev)
         rows["avg_reduce_sec7"] = timed(lambda: gq.avg_reduce(lvs, d, p, 0, norm, red, out), d * (K * lvb + lvb + 4.0))
     if pack == gq.GQ_PACK_I8 and d < (1 << 32):
-        # Algorithm 1 lines 6-8: compaction of every worker's non-zero codes, then the sum of the K lists
+        # Algorithm 1's sparse branch: compaction of every worker's non-zero codes, then the sum of the K lists
         cnts = [torch.zeros(1, dtype=torch.int64, device=dev) for _ in range(K)]
         ws = torch.empty(max(gq.compact_workspace_bytes(d), 4), dtype=torch.uint8, device=dev)
         probe_i = torch.empty(1, dtype=torch.int32, device=dev)

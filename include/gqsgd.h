@@ -68,16 +68,16 @@ typedef enum {
     GQ_ERR_DEVICE = 5        /* the HIP runtime reported an error at launch                          */
 } gq_status;
 
-/* Mixed norms ||[x_1..x_n]||_{q,p} of Section 4.1 that Algorithm 1 line 1 may use. */
+/* Mixed norms ||[x_1..x_n]||_{q,p} of Section 4.1 that Algorithm 1's norm step may use. */
 typedef enum {
     GQ_NORM_LINF = 0,   /* (inf,inf): max |x_ij| over all workers and coordinates (the paper's default) */
     GQ_NORM_L2 = 1,     /* (2,2):     L2 norm of the concatenation                                      */
-    GQ_NORM_L2_MAX = 2  /* (2,inf):   max over workers of ||x_i||_2 (line 1 read literally)             */
+    GQ_NORM_L2_MAX = 2  /* (2,inf):   max over workers of ||x_i||_2 (the norm step read literally)             */
 } gq_norm_kind;
 
 typedef enum { GQ_LINEAR = 0, GQ_EXP = 1 } gq_scheme;           /* level grid, Section 4.2 */
 
-/* Storage of the signed codes of one worker (Section 4.2 "8-bit", Section 7 "pack 4-bit into 8-bit").
+/* Storage of the signed codes of one worker (Section 4.2: 8-bit levels; Section 7: two 4-bit values packed into a byte).
  *   I8            byte j = q_j, two's complement                                       needs s <= 127
  *   I4            byte b = (q_2b & 15) | (q_2b+1 & 15) << 4, two's complement nibbles   needs s <= 7
  *                 (an odd d leaves the last high nibble 0)
@@ -113,7 +113,7 @@ gq_status gq_check_width(const gq_params *p /* host */, int K);
 /* Bytes of device workspace gq_global_norm needs for (K, d); 0 if K or d is out of range. */
 size_t gq_norm_workspace_bytes(int K, int64_t d);
 
-/* Algorithm 1 line 1: the global norm of K gradients of d coordinates each.
+/* Algorithm 1's norm step: the global norm of K gradients of d coordinates each.
  *   x             host array of K device pointers to fp32[d]
  *   norm_out      device fp32[1]: the norm, rounded once from a binary64 reduction (LINF is exact)
  *   status_flags  device uint32[1] or NULL: overwritten with bit0 = norm is not finite (a NaN or
@@ -125,7 +125,7 @@ gq_status gq_global_norm(const float *const *x /* host */, int K, int64_t d, gq_
                          float *norm_out, uint32_t *status_flags,
                          void *workspace, size_t workspace_bytes, void *hip_stream);
 
-/* Algorithm 1 lines 2-5 for ONE worker: y = |x|/norm, code = sign(x) * xi(y) (Definition 1, Eq. (2)).
+/* Algorithm 1's quantisation loop for ONE worker: y = |x|/norm, code = sign(x) * xi(y) (Definition 1, Eq. (2)).
  *   x              device fp32[d]
  *   norm           device fp32[1] (as written by gq_global_norm)
  *   worker         the worker word of the random stream (distinct workers round independently)
@@ -137,7 +137,7 @@ gq_status gq_quantize(const float *x, int64_t d, const float *norm, const gq_par
                       uint32_t worker, int64_t index_base,
                       void *levels_out, uint32_t *signplane_out, void *hip_stream);
 
-/* Algorithm 1 line 9 on one device: A_j = sum over the K workers of the integer value of the code.
+/* Algorithm 1's aggregation step on one device: A_j = sum over the K workers of the integer value of the code.
  *   levels      host array of K device pointers to level buffers in p->pack format
  *   signplanes  host array of K device pointers (the *_SIGNPLANE formats), else NULL
  *   agg_out     device int32[d] or int16[d] according to p->agg
@@ -199,7 +199,7 @@ gq_status gq_avg_reduce(const void *const *levels /* host */, int K, int64_t d, 
                         int64_t index_base, const float *norm, void *reduced_out, float *dequant_out,
                         void *hip_stream);
 
-/* Algorithm 1 lines 6-8, the sparse branch: only the non-zero codes are exchanged (Theorem 1 bounds their
+/* Algorithm 1's sparse branch: only the non-zero codes are exchanged (Theorem 1 bounds their
  * number under the (2,2) norm).  Sender side: the (coordinate index, signed code) pairs of the non-zero int8
  * codes of ONE worker, in increasing index order.
  *   levels           device int8[d] codes (p->pack must be GQ_PACK_I8; d <= 2^32 - 1, indices are 32-bit)

@@ -7,19 +7,19 @@
  * the order the paper states the steps, so that it can be checked against the paper by eye.
  *
  * What it follows (arXiv 2305.18627):
- *   Algorithm 1 line 1      global norm of the concatenation [x_1 .. x_n]          -> gqo_global_norm
- *   Algorithm 1 lines 2-5,  y = |x| / norm, z = sign(x) o xi(y) with the random
+ *   Algorithm 1, norm step  global norm of the concatenation [x_1 .. x_n]          -> gqo_global_norm
+ *   Algorithm 1, loop body, y = |x| / norm, z = sign(x) o xi(y) with the random
  *   Definition 1, Eq. (2)   rounding xi to one of the two neighbouring levels      -> gqo_linear_code, gqo_exp_code
  *   Section 4.2             linear grid l_i = (s-i)/s; exponential grid 0 and 2^-j -> same two functions
  *   Section 4.2 / Sec. 7    8-bit and packed 4-bit storage of the level integers   -> gqo_pack, gqo_unpack
- *   Algorithm 1 line 9      aggregation = plain sum of the level integers          -> gqo_aggregate
+ *   Algorithm 1, last step  aggregation = plain sum of the level integers          -> gqo_aggregate
  *   Section 4.2             headroom rule for the sum at a given integer width     -> gqo_check_width, gqo_fits_width
  *   Eq. (1)                 norm * (1/n) * sum                                     -> gqo_dequantize
  *   Algorithm 2, Sec. 4.3   reduce function on (sign, exponent) pairs, tree order  -> gqo_alg2_k, gqo_exp_reduce_pair,
  *                                                                                     gqo_exp_tree_reduce, gqo_exp_reduce_dequantize
  *   Section 7               low-bit linear codes averaged inside every reduce step -> gqo_avg_pair, gqo_avg_tree_reduce,
  *                                                                                     gqo_avg_reduce_dequantize
- *   Algorithm 1 lines 6-8   sparse branch: only the non-zero codes are exchanged   -> gqo_compact, gqo_sparse_aggregate
+ *   Algorithm 1, sparse branch: only the non-zero codes are exchanged              -> gqo_compact, gqo_sparse_aggregate
  *
  * Stored level integer ("code").  The paper numbers levels downwards, l_0 = 1 > ... > l_s = 0.
  * The integer that is stored and summed is k = s - u for level l_u, so k = 0 is the zero level:
@@ -32,7 +32,7 @@
  *   - exponential grid: printed as l_i = 1/2^(s-i), which contradicts l_0 = 1; the proof of
  *     Theorem 1 says the segment next to zero has length 2^-(s-1).  Grid used: {0} u {2^-j, j=0..s-1}.
  *   - "global L2 norm" is the (2,2) mixed norm = L2 norm of the concatenation; "global max norm"
- *     is (inf,inf).  (2,inf) = max of per-worker L2 norms (the literal line 1) is offered as well.
+ *     is (inf,inf).  (2,inf) = max of per-worker L2 norms (the norm step read literally) is offered as well.
  *   - exponential aggregation is the exact integer sum of V(k) (Algorithm 2's stochastic
  *     re-rounding is a different wire format and is not part of this path).
  *   - random numbers: Eq. (2) only fixes probabilities.  The draw is 32 bits r per (worker,
@@ -74,7 +74,7 @@
  *     range of the inputs.  Same tree as above (heap numbering, n' leaves, missing workers are zeros); the
  *     coin of node h at coordinate g is bit h mod 32 of the Philox word with counter
  *     (lo32(g/4), hi32(g/4), h / 32, 2), word g mod 4.  The root stands for the mean over n' leaves.
- *   - sparse branch (Algorithm 1 lines 6-8 say only "Allgather of the non-zero values"): a worker's message
+ *   - sparse branch (Algorithm 1 says only that the non-zero values are all-gathered): a worker's message
  *     is the list of (coordinate index, signed code) of its non-zero codes in increasing index order, and the
  *     receiver adds the integer values of all K lists into a dense sum, which equals the dense aggregate.
  *   - top of the range: |x| = norm can land one ulp above s after rounding; the code is clamped to s.
@@ -159,7 +159,7 @@ void gqo_random_words(uint64_t seed, uint32_t worker, uint64_t index_base, int64
 }
 
 /* ------------------------------------------------------------------------------------------
- * Algorithm 1 line 1: the global norm.  Returns flag bits: 1 = norm not finite, 2 = norm zero.
+ * Algorithm 1's norm step: the global norm.  Returns flag bits: 1 = norm not finite, 2 = norm zero.
  * ------------------------------------------------------------------------------------------ */
 int gqo_global_norm(const float *const *x, int K, int64_t d, int kind, double *norm_exact, float *norm_f32)
 {
@@ -253,7 +253,7 @@ void gqo_quantize_with_words(const float *x, const uint32_t *r, int64_t d, float
     for (int64_t j = 0; j < d; j++) q[j] = gqo_code(scheme, x[j], norm, s, r[j]);
 }
 
-/* Algorithm 1 lines 2-5 for one worker. */
+/* Algorithm 1's quantisation loop for one worker. */
 void gqo_quantize(const float *x, int64_t d, float norm, int scheme, int s,
                   uint64_t seed, uint32_t worker, uint64_t index_base, int rng_bits, int32_t *q)
 {
@@ -270,7 +270,7 @@ int64_t gqo_code_value(int scheme, int32_t q)
     return q < 0 ? -v : v;
 }
 
-/* Algorithm 1 line 9: A_j = sum_i V(q_ij), accumulated in 64 bits. */
+/* Algorithm 1's aggregation step: A_j = sum_i V(q_ij), accumulated in 64 bits. */
 void gqo_aggregate(const int32_t *const *q, int K, int64_t d, int scheme, int64_t *A)
 {
     for (int64_t j = 0; j < d; j++) {
@@ -386,7 +386,7 @@ int gqo_quantize_aggregate(const float *const *x, int K, int64_t d, float norm, 
  * A pair (sign, e), sign in {-1,+1}, e >= 0, stands for 0 if e = 0 and for sign * 2^-e otherwise.
  * ========================================================================================== */
 
-/* The random integer k of Algorithm 2 line 1: P(k > b) = 2^-b.  With p = r / 2^32,
+/* The random integer k of Algorithm 2: P(k > b) = 2^-b.  With p = r / 2^32,
  * k > b  <=>  p < 2^-b  <=>  r has at least b leading zero bits. */
 int gqo_alg2_k(uint32_t r)
 {
@@ -395,7 +395,7 @@ int gqo_alg2_k(uint32_t r)
     return lz + 1;
 }
 
-/* Algorithm 2 lines 2-9, in the listing's notation. */
+/* Algorithm 2, the reduction of one pair, in the paper's notation. */
 void gqo_exp_reduce_pair(int sign1, int e1, int sign2, int e2, int k, int *sign_result, int *e_result)
 {
     int e1_nonzero = e1 > 0;
@@ -490,7 +490,7 @@ void gqo_avg_reduce_dequantize(const int32_t *code, int64_t d, double norm, int 
 }
 
 /* ==========================================================================================
- * Algorithm 1 lines 6-8: the sparse branch.  What a worker sends is the list of its non-zero
+ * Algorithm 1's sparse branch.  What a worker sends is the list of its non-zero
  * codes with their coordinate indices, in increasing index order; what every receiver forms from
  * the K lists is the same integer sum as the dense aggregate.
  * ========================================================================================== */

@@ -109,7 +109,7 @@ def random_words(seed, worker, index_base, d, rng_bits=32):
 
 
 def global_norm(xs, kind):
-    """Algorithm 1 line 1.  Returns (norm in binary64, norm rounded to binary32, flag bits)."""
+    """Algorithm 1's norm step.  Returns (norm in binary64, norm rounded to binary32, flag bits)."""
     rows, ptrs, K, d = _rows(xs, np.float32, C.c_float)
     ne = C.c_double(0.0); nf = C.c_float(0.0)
     flags = _global_norm(ptrs, K, d, int(kind), C.byref(ne), C.byref(nf))
@@ -133,7 +133,7 @@ def quantize_with_words(x, r, norm, scheme, s):
 
 
 def quantize(x, norm, scheme, s, seed, worker, index_base=0, rng_bits=32):
-    """Algorithm 1 lines 2-5 for one worker: signed level integers, one int32 per coordinate."""
+    """Algorithm 1's quantisation loop for one worker: signed level integers, one int32 per coordinate."""
     x = _arr(x, np.float32).reshape(-1)
     q = np.zeros(x.shape[0], np.int32)
     _quantize(_ptr(x, C.c_float), x.shape[0], float(np.float32(norm)), int(scheme), int(s),
@@ -147,7 +147,7 @@ def code_value(scheme, q):
 
 
 def aggregate(qs, scheme):
-    """Algorithm 1 line 9: the integer sum over workers, in int64."""
+    """Algorithm 1's aggregation step: the integer sum over workers, in int64."""
     rows, ptrs, K, d = _rows(qs, np.int32, C.c_int32)
     A = np.zeros(d, np.int64)
     _aggregate(ptrs, K, d, int(scheme), _ptr(A, C.c_int64))
@@ -208,12 +208,12 @@ def quantize_aggregate(xs, norm, scheme, s, seed, index_base=0, rng_bits=32):
 
 
 def alg2_k(r):
-    """Algorithm 2 line 1: the random integer k with P(k > b) = 2^-b, from a 32-bit word."""
+    """Algorithm 2: the random integer k with P(k > b) = 2^-b, from a 32-bit word."""
     return int(_alg2_k(int(r)))
 
 
 def exp_reduce_pair(sign1, e1, sign2, e2, k):
-    """Algorithm 2 lines 2-9 on (sign, e) pairs standing for sign * 2^-e (e = 0: zero)."""
+    """Algorithm 2, the reduction of one pair, on (sign, e) pairs standing for sign * 2^-e (e = 0: zero)."""
     sr, er = C.c_int(0), C.c_int(0)
     _exp_reduce_pair(int(sign1), int(e1), int(sign2), int(e2), int(k), C.byref(sr), C.byref(er))
     return sr.value, er.value
@@ -262,7 +262,7 @@ def avg_reduce_dequantize(code, norm, s, K):
 
 
 def compact(q, capacity=None):
-    """Algorithm 1 lines 6-8, sender side: (count, indices, codes) of the non-zero codes, by increasing index.
+    """Algorithm 1's sparse branch, sender side: (count, indices, codes) of the non-zero codes, by increasing index.
     At most `capacity` pairs are returned; count is always the true number."""
     q = _arr(q, np.int32).reshape(-1)
     cap = q.shape[0] if capacity is None else int(capacity)
@@ -273,7 +273,7 @@ def compact(q, capacity=None):
 
 
 def sparse_aggregate(indices, codes, d, scheme):
-    """Algorithm 1 lines 6-8, receiver side: the dense integer sum formed from K lists."""
+    """Algorithm 1's sparse branch, receiver side: the dense integer sum formed from K lists."""
     K = len(indices)
     ii = [_arr(a, np.uint32).reshape(-1) for a in indices]
     cc = [_arr(a, np.int32).reshape(-1) for a in codes]

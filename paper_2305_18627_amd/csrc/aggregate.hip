@@ -1,4 +1,4 @@
-// Algorithm 1 line 9 and Eq. (1) on MI355X (gfx950): the integer sum of stored codes and its
+// Algorithm 1's aggregation step and Eq. (1) on MI355X (gfx950): the integer sum of stored codes and its
 // dequantisation.  The contract of the entry points is stated in include/gqsgd.h.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -11,7 +11,7 @@
 namespace gq {
 
 // =============================================================================================
-// Algorithm 1 line 9 on stored codes.  Same ownership as the fused kernel: a lane owns four
+// Algorithm 1's aggregation step on stored codes.  Same ownership as the fused kernel: a lane owns four
 // coordinates, i.e. one 32-bit (8-bit codes) or 16-bit (4-bit codes) word of every worker's level
 // buffer and a nibble of its sign words; loads and the 128-bit stores of a wave are contiguous.
 // =============================================================================================
@@ -134,7 +134,7 @@ int_aggregate_kernel(LevelCPtrs L, int K, int64_t d, int64_t v_begin, void *__re
 }
 
 // =============================================================================================
-// Algorithm 1 line 9 on packed 4-bit codes, for workgroups that lie wholly inside the buffer.  The
+// Algorithm 1's aggregation step on packed 4-bit codes, for workgroups that lie wholly inside the buffer.  The
 // one-vector-per-lane kernel above moves two bytes per lane and load, which leaves it bound by
 // instruction issue, not by HBM.  Here a lane owns EIGHT coordinates: one 32-bit load of codes (and one
 // byte of sign bits) per worker.  Every byte of codes, together with its two sign bits in the sign-plane

@@ -61,7 +61,7 @@ __device__ __forceinline__ Words4 random_words(uint64_t seed, uint32_t worker, u
 }
 
 // ---------------------------------------------------------------------------------------------
-// Per-call constants derived from the norm on the device (Algorithm 1 line 3, y = |x| / norm).
+// Per-call constants derived from the norm on the device (Algorithm 1's normalisation, y = |x| / norm).
 // ---------------------------------------------------------------------------------------------
 struct Scale {
     float scale;   // s / norm (linear) or 2^(s-1) / norm (exponential); 0 if the norm is unusable

@@ -1,4 +1,4 @@
-// Algorithm 1 line 1 on MI355X (gfx950): the global norm of K resident gradients.
+// Algorithm 1's norm step on MI355X (gfx950): the global norm of K resident gradients.
 // The contract of the entry points is stated in include/gqsgd.h.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -11,7 +11,7 @@
 namespace gq {
 
 // =============================================================================================
-// Algorithm 1 line 1: global norm.  Pass 1 reduces the gradients to 8-byte partials (a uint32 bit
+// Algorithm 1's norm step: global norm.  Pass 1 reduces the gradients to 8-byte partials (a uint32 bit
 // pattern for the max norm, a binary64 sum of squares otherwise); pass 2 folds the partials in a
 // fixed order in one block and writes the norm and the status word.  No atomics: reproducible.
 //

@@ -1,4 +1,4 @@
-// Algorithm 1 lines 2-5 (and line 9 fused in) on MI355X (gfx950): stochastic rounding of the gradients
+// Algorithm 1's quantisation loop (with its aggregation step fused in) on MI355X (gfx950): stochastic rounding of the gradients
 // to integer codes, for one worker with the codes stored, or for all K workers with the integer sum
 // formed in registers.  The contract of the entry points is stated in include/gqsgd.h.
 //
@@ -19,7 +19,7 @@
 namespace gq {
 
 // =============================================================================================
-// Algorithm 1 lines 2-5 and 9 fused: quantize the K workers' coordinates in registers, add the
+// Algorithm 1's quantisation loop and aggregation step fused: quantize the K workers' coordinates in registers, add the
 // integer values, write the sum (and/or its dequantised mean, Eq. (1), and/or the packed codes).
 //   SCHEME      0 linear, 1 exponential
 //   KT          compile-time worker count (fully unrolled, K loads in flight), 0 = run-time K
@@ -326,7 +326,7 @@ quantize_aggregate_kernel(GradPtrs P, LevelPtrs L, int K, int64_t d, int64_t v0,
 }
 
 // =============================================================================================
-// Algorithm 1 lines 2-5 for one worker with the codes stored: a lane owns kQuantVec vectors of four
+// Algorithm 1's quantisation loop for one worker with the codes stored: a lane owns kQuantVec vectors of four
 // coordinates, kQuantBlock vectors apart (short draws: two pairs 64 apart, see share_short_draws), and
 // issues all its loads before the first Philox call.
 // =============================================================================================

@@ -1,4 +1,4 @@
-// Algorithm 1 lines 6-8 on MI355X (gfx950): compaction of non-zero codes and the sum of the K lists.
+// Algorithm 1's sparse branch on MI355X (gfx950): compaction of non-zero codes and the sum of the K lists.
 // Contracts: include/gqsgd.h.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -11,7 +11,7 @@
 namespace gq {
 
 // =============================================================================================
-// Algorithm 1 lines 6-8, the sparse branch.  Sender side: the (index, code) pairs of a worker's
+// Algorithm 1's sparse branch, the sparse branch.  Sender side: the (index, code) pairs of a worker's
 // non-zero int8 codes in increasing index order, by a count pass, a one-block scan of the block
 // counts and a write pass that ranks the non-zeros inside a block with wave scans.  Receiver side:
 // the K sorted lists are merged tile by tile into the dense int32 sum.

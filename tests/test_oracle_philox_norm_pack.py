@@ -58,7 +58,7 @@ def test_random_words_look_uniform_and_workers_differ():
     assert abs((u[:-1] * u[1:]).mean()) < 5.0 / (12.0 * np.sqrt(n))
 
 
-# ---------------------------------------------------------------- norm (Algorithm 1 line 1)
+# ---------------------------------------------------------------- norm (Algorithm 1's norm step)
 def test_norm_against_numpy_bruteforce():
     rng = np.random.default_rng(1)
     xs = [rng.normal(0, 1e-3, 5001).astype(np.float32) for _ in range(5)]

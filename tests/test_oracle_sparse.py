@@ -1,4 +1,4 @@
-"""Pins for the oracle's sparse branch (arXiv 2305.18627, Algorithm 1 lines 6-8; Theorem 1's sparsity
+"""Pins for the oracle's sparse branch (arXiv 2305.18627, Algorithm 1's sparse branch; Theorem 1's sparsity
 statement for p = q = 2).  Expected values: numpy's nonzero, the dense aggregate, and the expected
 number of non-zero codes that Eq. (2) implies."""
 import math
