@@ -395,18 +395,34 @@ int gqo_alg2_k(uint32_t r)
     return lz + 1;
 }
 
-/* Algorithm 2, the reduction of one pair, in the paper's notation. */
+/* Algorithm 2, the reduction of one pair (Section 4.3): x1 + x2 for x = sign * 2^-e (e = 0: zero), rounded at
+ * random to a neighbouring power of two so that the expectation is the exact sum.  k is the random integer
+ * above.  Written out case by case from the derivation in the text:
+ *   - a zero operand leaves the other one unchanged;
+ *   - otherwise let a be the operand of larger magnitude (smaller exponent, operand 1 on a tie), b the
+ *     other, and gap = e_b - e_a >= 0;
+ *   - equal signs: |x1 + x2| = 2^-e_a (1 + 2^-gap) lies a fraction 2^-gap of the way from 2^-e_a up to
+ *     2^-(e_a - 1), so it goes up with probability 2^-gap = P(k > gap);
+ *   - opposite signs: gap = 0 cancels exactly; else |x1 + x2| = 2^-e_a (1 - 2^-gap) lies a fraction
+ *     2^-(gap-1) of the way from 2^-e_a down to 2^-(e_a + 1), so it goes down with probability P(k > gap - 1);
+ *   - the sign is that of a. */
 void gqo_exp_reduce_pair(int sign1, int e1, int sign2, int e2, int k, int *sign_result, int *e_result)
 {
-    int e1_nonzero = e1 > 0;
-    int e2_nonzero = e2 > 0;
-    int sign12 = sign1 * sign2 * e1_nonzero * e2_nonzero;
-    int absdiff = e1 > e2 ? e1 - e2 : e2 - e1;
-    int diff = absdiff - (1 - sign12) / 2;
-    int smaller = ((e1 <= e2) + !e2_nonzero) * e1_nonzero;
-    int nonzero = 1 - (e1 == e2 && sign12 == -1);
-    *sign_result = sign1 * smaller + sign2 * (1 - smaller);
-    *e_result = (e1 * smaller + e2 * (1 - smaller)) * nonzero - sign12 * (k > diff) * nonzero;
+    if (e1 == 0) { *sign_result = sign2; *e_result = e2; return; }
+    if (e2 == 0) { *sign_result = sign1; *e_result = e1; return; }
+    int first_is_a = e1 <= e2;
+    int sign_a = first_is_a ? sign1 : sign2;
+    int e_a = first_is_a ? e1 : e2;
+    int e_b = first_is_a ? e2 : e1;
+    int gap = e_b - e_a;
+    *sign_result = sign_a;
+    if (sign1 == sign2) {
+        *e_result = (k > gap) ? e_a - 1 : e_a;
+    } else if (gap == 0) {
+        *e_result = 0;
+    } else {
+        *e_result = (k > gap - 1) ? e_a + 1 : e_a;
+    }
 }
 
 static int ceil_log2_int(int n) { int l = 0; while ((1 << l) < n) l++; return l; }
