@@ -126,13 +126,15 @@ template <> struct Acc<1> {
 // kWindowTicksPerWorker * K ticks, and stores then: the chip alternates between a long stretch of pure
 // reads and a short burst of writes (6.3-6.5 TB/s for K >= 12).  The period is the time one
 // generation of resident waves needs for its K loads, so a wave waits for about one window, not more.
-// The wait is bounded (at most 4096 polls) and touches no memory, so it changes timing only.  For this
+// The wait is bounded (at most kWindowMaxPolls polls, a few periods even at K = 64) and touches no memory, so it
+// changes timing only: if the counter did not advance, a wave would lose about 0.25 ms and go on.  For this
 // to work the loads of a lane must really stay few in flight: the accumulators are pinned after each
 // batch of four workers, which stops the compiler from hoisting all K loads to the top (it would
 // otherwise, and with every load issued up front the windows were measured to gain nothing).
 constexpr uint32_t kWindowTicksPerWorker = 62;    // ticks of the 100 MHz counter per worker and period
 constexpr int kWindowMinWorkers = 8;
 constexpr double kWindowMinLoads = 2.5e8;         // K * d from which the windows win (measured)
+constexpr int kWindowMaxPolls = 1024;             // polls of about 0.2 us each: the longest period (K = 64, short draws) is 79 us
 
 // Short draws (16 random bits per coordinate): one Philox call serves the eight coordinates of two
 // neighbouring vectors 2c and 2c+1.  To keep every load and store of a wave contiguous, a wave takes 128
@@ -277,7 +279,7 @@ quantize_aggregate_kernel(GradPtrs P, LevelPtrs L, int K, int64_t d, int64_t v0,
     if (nvalid[0] == 0) return;
 
     if (WINDOWS) {
-        for (int it = 0; it < 4096; it++) {
+        for (int it = 0; it < kWindowMaxPolls; it++) {
             const uint32_t t = (uint32_t)__builtin_amdgcn_s_memrealtime();
             if ((t % win_period) < win_open) break;
             __builtin_amdgcn_s_sleep(8);
