@@ -364,6 +364,43 @@ def test_fused_matches_oracle(scheme, s, pack, agg, K, d):
     assert np.array_equal(host(d_only)[:d], host(deq_out)[:d])
 
 
+@pytest.mark.parametrize("rng_bits", [32, 16])
+def test_fused_degenerate_inputs(rng_bits):
+    # the degenerate cases of the method: an all-zero gradient (norm 0), unusable norms, identical workers,
+    # one non-zero coordinate sitting on the norm
+    K, d = 4, 10_007
+    for scheme, s in ((0, 127), (1, 16)):
+        p = gq.make_params(scheme, s, 0, 0, seed=3, rng_bits=rng_bits)
+        zeros = [torch.zeros(d, device=DEV) for _ in range(K)]
+        norm_t = dev_scalar(-1.0)
+        flags = torch.zeros(1, dtype=torch.int32, device=DEV)
+        gq.global_norm(zeros, NORMS["l2"], norm_t, flags)
+        assert float(norm_t.item()) == 0.0 and int(flags.item()) == 2
+        agg, deq, lvs, _ = run_fused(zeros, norm_t, p, 0, True)
+        assert bool((agg[:d] == 0).all()) and bool((deq[:d] == 0).all()) and all(bool((l[:d] == 0).all()) for l in lvs)
+        xs = gaussians(K, d, seed=8)
+        for bad in (0.0, float("nan"), float("inf"), -1.0):
+            agg, deq, lvs, _ = run_fused(xs, dev_scalar(bad), p, 0, True)
+            assert bool((agg[:d] == 0).all()) and bool((deq[:d] == 0).all()) and all(bool((l[:d] == 0).all()) for l in lvs)
+            assert np.all(O.quantize_aggregate([host(x) for x in xs], np.float32(bad), scheme, s, 3, 0, rng_bits=rng_bits) == 0)
+        # identical workers still round independently (the worker word is part of the counter), and the sum of
+        # the K copies equals the oracle's
+        same = [xs[0]] * K
+        _, nf, _ = oracle_norm(same, NORMS["linf"])
+        agg, _, lvs, _ = run_fused(same, dev_scalar(float(nf)), p, 0, True)
+        want = O.quantize_aggregate([host(xs[0])] * K, nf, scheme, s, 3, 0, rng_bits=rng_bits)
+        assert np.array_equal(host(agg)[:d].astype(np.int64), want)
+        assert not torch.equal(lvs[0][:d], lvs[1][:d])
+        # a single non-zero coordinate: y = 1 there, the top level with certainty; everything else stays zero
+        one = [torch.zeros(d, device=DEV) for _ in range(K)]
+        one[2][4321] = -0.75
+        gq.global_norm(one, NORMS["linf"], norm_t, flags)
+        agg, deq, _, _ = run_fused(one, norm_t, p, 0, False)
+        top = s if scheme == 0 else 2 ** (s - 1)
+        assert int(agg[4321].item()) == -top and int(agg.abs()[:d].sum().item()) == top
+        assert abs(float(deq[4321].item()) - (-0.75 / K)) <= RTOL * 0.75 / K
+
+
 def test_fused_equals_separate_calls_and_buckets_equal_whole():
     K, d = 8, 300_007
     xs = gaussians(K, d, seed=77)
