@@ -21,9 +21,10 @@
  *              reported through the device word `status_flags` of gq_global_norm.
  *   sizes      1 <= K <= GQ_MAX_WORKERS, d >= 0 (d = 0 is a valid no-op), any d (ragged tails are
  *              handled inside), index_base >= 0 and a multiple of 4 (of 8 with rng_bits = 16).
- *              gq_fused_quantize_aggregate with rng_bits = 32 and no stored codes takes any d; every other
- *              call takes at least d <= 2^34 - 1024 coordinates per call and answers GQ_ERR_INVALID_ARG
- *              where a single launch could not cover more (cut longer gradients into buckets).
+ *              gq_fused_quantize_aggregate with rng_bits = 32 and no stored codes takes any d.  Every
+ *              other call accepts any d up to 2^34 - 1024 coordinates (the sparse branch: 2^32 - 1) and
+ *              answers GQ_ERR_INVALID_ARG beyond what one launch can cover: cut longer gradients into
+ *              buckets and pass their offsets as index_base.
  *
  * The stored integer ("code").  The paper numbers levels downwards, l_0 = 1 > ... > l_s = 0
  * (Definition 1).  The integer stored and summed is k = s - u for level l_u, signed with sign(x):
