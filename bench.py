@@ -281,6 +281,9 @@ def main():
                        "dequantize": (b_deq / float(np.mean(t_deq)) * 1e-6) if b_deq else None},
         "norm_flags": int(flags.item()),
     }
+    if 4.0 * K * d <= 256e6:
+        line["config"]["note"] = ("the inputs (%.0f MB) fit the 256 MB last-level cache and every call is launch-bound: "
+                                  "not an HBM figure" % (4.0 * K * d / 1e6))
     if args.graph:
         # the calls only enqueue (no allocation, no synchronisation), so the step can be captured once and replayed:
         # what a launch-bound caller (small d) gains from that
