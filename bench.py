@@ -26,7 +26,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X: 8 TB/s HBM3E (published peak)
-TRAFFIC_FILE = os.path.join(ROOT, "profiles", "fused_quantize_aggregate_c3_traffic.json")
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "fused_quantize_aggregate_c3_traffic_figures.txt")
 
 
 def parse():
