@@ -99,7 +99,7 @@ __device__ __forceinline__ void store_codes(void *lv, uint32_t *sp, int pack, in
 }
 
 // Threads per workgroup of the fused kernel.  Small groups retire and refill wave slots at a finer
-// grain, which measurably helps the HBM read/write mix of this kernel (64 > 128 > 256 on MI355X).
+// grain, which measurably helps the HBM read/write mix of this kernel (128 and 64 alike, 256 slower on MI355X).
 constexpr int kFusedBlock = 128;
 
 // The integer sum of one lane's four coordinates.  Linear codes are summed as floats (exact: the
