@@ -148,9 +148,9 @@ def time_rows(gq, torch, xs, norm, params, cfg, args):
         rows["exp_reduce_alg2"]["coords_per_s"] = d / rows["exp_reduce_alg2"]["ms"] * 1e3
         rows["exp_reduce_alg2"]["tree_nodes_per_coordinate"] = npad - 1
     if params.scheme == gq.GQ_LINEAR and pack in (gq.GQ_PACK_I8, gq.GQ_PACK_I4):
-        # Section 7: averaging inside every reduce step; codes in, one code vector and the fp32 mean out
+        # Implementation section: averaging inside every reduce step; codes in, one code vector and the fp32 mean out
         red = torch.empty(gq.levels_nbytes(d, pack), dtype=torch.uint8, device=dev)
-        rows["avg_reduce_sec7"] = timed(lambda: gq.avg_reduce(lvs, d, p, 0, norm, red, out), d * (K * lvb + lvb + 4.0))
+        rows["avg_reduce_in_step"] = timed(lambda: gq.avg_reduce(lvs, d, p, 0, norm, red, out), d * (K * lvb + lvb + 4.0))
     if pack == gq.GQ_PACK_I8 and d < (1 << 32):
         # Algorithm 1's sparse branch: compaction of every worker's non-zero codes, then the sum of the K lists
         cnts = [torch.zeros(1, dtype=torch.int64, device=dev) for _ in range(K)]

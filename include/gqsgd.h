@@ -78,7 +78,7 @@ typedef enum {
 
 typedef enum { GQ_LINEAR = 0, GQ_EXP = 1 } gq_scheme;           /* level grid, Section 4.2 */
 
-/* Storage of the signed codes of one worker (Section 4.2: 8-bit levels; Section 7: two 4-bit values packed into a byte).
+/* Storage of the signed codes of one worker (Section 4.2: 8-bit levels; Implementation section: two 4-bit values packed into a byte).
  *   I8            byte j = q_j, two's complement                                       needs s <= 127
  *   I4            byte b = (q_2b & 15) | (q_2b+1 & 15) << 4, two's complement nibbles   needs s <= 7
  *                 (an odd d leaves the last high nibble 0)
@@ -185,7 +185,7 @@ gq_status gq_exp_reduce(const void *const *levels /* host */, int K, int64_t d, 
                         int64_t index_base, const float *norm, void *reduced_out, float *dequant_out,
                         void *hip_stream);
 
-/* Section 7, low-bit linear dithering: the average is taken inside every reduce step instead of summing
+/* Implementation section, low-bit linear dithering: the average is taken inside every reduce step instead of summing
  * until the end, so the codes never leave their b bits (a 4-bit sum over 4 workers would leave one value
  * bit).  Same tree as gq_exp_reduce (n' = K rounded up to a power of two, heap numbering, missing workers
  * are zeros).  A node holds round((a + b) / 2); an odd sum is rounded up iff its coin is set, the coin of

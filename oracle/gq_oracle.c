@@ -11,13 +11,13 @@
  *   Algorithm 1, loop body, y = |x| / norm, z = sign(x) o xi(y) with the random
  *   Definition 1, Eq. (2)   rounding xi to one of the two neighbouring levels      -> gqo_linear_code, gqo_exp_code
  *   Section 4.2             linear grid l_i = (s-i)/s; exponential grid 0 and 2^-j -> same two functions
- *   Section 4.2 / Sec. 7    8-bit and packed 4-bit storage of the level integers   -> gqo_pack, gqo_unpack
+ *   Sec. 4.2, Implementation 8-bit and packed 4-bit storage of the level integers   -> gqo_pack, gqo_unpack
  *   Algorithm 1, last step  aggregation = plain sum of the level integers          -> gqo_aggregate
  *   Section 4.2             headroom rule for the sum at a given integer width     -> gqo_check_width, gqo_fits_width
  *   Eq. (1)                 norm * (1/n) * sum                                     -> gqo_dequantize
  *   Algorithm 2, Sec. 4.3   reduce function on (sign, exponent) pairs, tree order  -> gqo_alg2_k, gqo_exp_reduce_pair,
  *                                                                                     gqo_exp_tree_reduce, gqo_exp_reduce_dequantize
- *   Section 7               low-bit linear codes averaged inside every reduce step -> gqo_avg_pair, gqo_avg_tree_reduce,
+ *   Implementation section  low-bit linear codes averaged inside every reduce step -> gqo_avg_pair, gqo_avg_tree_reduce,
  *                                                                                     gqo_avg_reduce_dequantize
  *   Algorithm 1, sparse branch: only the non-zero codes are exchanged              -> gqo_compact, gqo_sparse_aggregate
  *
@@ -68,7 +68,7 @@
  *     leaf n' + i, missing workers are zeros); operand 1 of a node is its child 2h.
  *     In the second-sign case the probability is printed as 2^(e2-e1-1); the text's equivalent form
  *     "k > e2 - e1 - 1" and unbiasedness both give 2^-(e2-e1-1), which is what the listing computes.
- *   - averaging inside each reduce step (Section 7 says only that the average replaces the sum in every
+ *   - averaging inside each reduce step (the Implementation section says only that the average replaces the sum in every
  *     step and that each step rounds): a node holds round((a + b) / 2) of its two children, an odd sum
  *     being rounded up or down with probability 1/2 each, which keeps the result unbiased and inside the
  *     range of the inputs.  Same tree as above (heap numbering, n' leaves, missing workers are zeros); the
@@ -471,7 +471,7 @@ void gqo_exp_reduce_dequantize(const int32_t *se, int64_t d, double norm, int K,
 }
 
 /* ==========================================================================================
- * Section 7: for low-bit linear dithering the paper averages inside every reduce step instead of
+ * Implementation section: for low-bit linear dithering the paper averages inside every reduce step instead of
  * summing until the end, so that the codes never leave their b bits.
  * ========================================================================================== */
 

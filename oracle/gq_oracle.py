@@ -241,7 +241,7 @@ def exp_reduce_dequantize(se, norm, K):
 
 
 def avg_pair(a, b, coin):
-    """Section 7, one reduce step with averaging: round((a+b)/2), an odd sum going up iff coin."""
+    """Implementation section, one reduce step with averaging: round((a+b)/2), an odd sum going up iff coin."""
     return int(_avg_pair(int(a), int(b), int(coin)))
 
 

@@ -85,13 +85,21 @@ __device__ __forceinline__ Scale make_scale(float norm, int s)
 // ---------------------------------------------------------------------------------------------
 template <int SCHEME> struct Round;
 
+// min(t, top) for t >= -0, and 0 for a NaN t (a NaN or Inf coordinate times a zero scale, or a NaN
+// coordinate): v_med3_f32 returns the smallest of its non-NaN operands when one operand is a NaN, so the
+// clamp at the top level and the "a NaN rounds to code 0" rule cost one instruction together.
+__device__ __forceinline__ float clamp_nan_to_zero(float t, float top)
+{
+    return __builtin_amdgcn_fmed3f(t, 0.0f, top);
+}
+
 // Linear grid l_u = (s-u)/s: t = y*s lies between h and h+1; the upper one is taken iff U' < t-h.
 template <> struct Round<0> {
     static __device__ __forceinline__ float value(float x, const Scale &sc, uint32_t r)
     {
         const float u = (float)r * 0x1.fffffep-33f;                       // U' in [0,1)
         const float v = __builtin_fmaf(__builtin_fabsf(x), sc.scale, -u); // t - U', one rounding
-        const float c = __builtin_fminf(__builtin_ceilf(v), sc.top);      // clamp at the top level
+        const float c = clamp_nan_to_zero(__builtin_ceilf(v), sc.top);   // clamp at the top level
         return __builtin_copysignf(c, x);
     }
     static __device__ __forceinline__ int code_of_value(float value) { return (int)value; }
@@ -103,7 +111,7 @@ template <> struct Round<0> {
 template <> struct Round<1> {
     static __device__ __forceinline__ float value(float x, const Scale &sc, uint32_t r)
     {
-        const float z = __builtin_fminf(__builtin_fabsf(x) * sc.scale, sc.top);
+        const float z = clamp_nan_to_zero(__builtin_fabsf(x) * sc.scale, sc.top);
         const float one = z < 1.0f ? 1.0f : 0.0f;
         const float w = z + one;
         const uint32_t b = __float_as_uint(w) + (r >> 9);
@@ -121,7 +129,7 @@ template <> struct Round<1> {
     // k = E - 126 for z >= 1 (value 2^(E-127)), k = E - 127 for z < 1 (value 0 or 1).
     static __device__ __forceinline__ int code(float x, const Scale &sc, uint32_t r)
     {
-        const float z = __builtin_fminf(__builtin_fabsf(x) * sc.scale, sc.top);
+        const float z = clamp_nan_to_zero(__builtin_fabsf(x) * sc.scale, sc.top);
         const bool small = z < 1.0f;
         const float w = z + (small ? 1.0f : 0.0f);
         const uint32_t b = __float_as_uint(w) + (r >> 9);

@@ -207,36 +207,11 @@ norm_final_kernel(const uint64_t *__restrict__ partial, int groups, int64_t per_
     }
 }
 
-}  // namespace gq
-
-using namespace gq;
-
-extern "C" {
-
-size_t gq_norm_workspace_bytes(int K, int64_t d)
+// The launches of gq_global_norm, shared by both entry points: `partial` holds at least
+// gq_norm_workspace_bytes(K, d) bytes.  Arguments other than `partial` have been checked.
+static gq_status launch_global_norm(const GradPtrs &P, int K, int64_t d, gq_norm_kind kind, float *norm_out,
+                                    uint32_t *status_flags, uint64_t *partial, hipStream_t st)
 {
-    if (K < 1 || K > GQ_MAX_WORKERS || d < 0) return 0;
-    int64_t blocks, tpb;
-    norm_tile_shape(d, &blocks, &tpb);
-    const size_t per_worker = (size_t)K * (size_t)norm_blocks_per_worker(d);
-    return (per_worker > (size_t)blocks ? per_worker : (size_t)blocks) * sizeof(uint64_t);
-}
-
-gq_status gq_global_norm(const float *const *x, int K, int64_t d, gq_norm_kind kind, float *norm_out,
-                         uint32_t *status_flags, void *workspace, size_t workspace_bytes, void *hip_stream)
-{
-    if (!x || K < 1 || K > GQ_MAX_WORKERS || d < 0) return GQ_ERR_INVALID_ARG;
-    if (kind != GQ_NORM_LINF && kind != GQ_NORM_L2 && kind != GQ_NORM_L2_MAX) return GQ_ERR_INVALID_ARG;
-    if (!aligned(norm_out, 4) || (status_flags && !aligned(status_flags, 4))) return GQ_ERR_INVALID_ARG;
-    GradPtrs P;
-    for (int i = 0; i < K; i++) {
-        if (d > 0 && !aligned(x[i], 16)) return GQ_ERR_INVALID_ARG;
-        P.x[i] = x[i];
-    }
-    if (!workspace || workspace_bytes < gq_norm_workspace_bytes(K, d)) return GQ_ERR_WORKSPACE;
-    if (!aligned(workspace, 8)) return GQ_ERR_INVALID_ARG;
-    hipStream_t st = (hipStream_t)hip_stream;
-    uint64_t *partial = reinterpret_cast<uint64_t *>(workspace);
     int groups = 1;
     int64_t per_group = 0;
     if (d > 0 && kind == GQ_NORM_L2_MAX) {
@@ -264,6 +239,46 @@ gq_status gq_global_norm(const float *const *x, int K, int64_t d, gq_norm_kind k
     hipLaunchKernelGGL(norm_final_kernel, dim3(1), dim3(kNormFinalBlock), 0, st, partial, groups, per_group, (int)kind,
                        norm_out, status_flags);
     return launched();
+}
+
+static gq_status check_global_norm_args(const float *const *x, int K, int64_t d, gq_norm_kind kind, const float *norm_out,
+                                        const uint32_t *status_flags, GradPtrs *P)
+{
+    if (!x || K < 1 || K > GQ_MAX_WORKERS || d < 0) return GQ_ERR_INVALID_ARG;
+    if (kind != GQ_NORM_LINF && kind != GQ_NORM_L2 && kind != GQ_NORM_L2_MAX) return GQ_ERR_INVALID_ARG;
+    if (!aligned(norm_out, 4) || (status_flags && !aligned(status_flags, 4))) return GQ_ERR_INVALID_ARG;
+    for (int i = 0; i < K; i++) {
+        if (d > 0 && !aligned(x[i], 16)) return GQ_ERR_INVALID_ARG;
+        P->x[i] = x[i];
+    }
+    return GQ_OK;
+}
+
+}  // namespace gq
+
+using namespace gq;
+
+extern "C" {
+
+size_t gq_norm_workspace_bytes(int K, int64_t d)
+{
+    if (K < 1 || K > GQ_MAX_WORKERS || d < 0) return 0;
+    int64_t blocks, tpb;
+    norm_tile_shape(d, &blocks, &tpb);
+    const size_t per_worker = (size_t)K * (size_t)norm_blocks_per_worker(d);
+    return (per_worker > (size_t)blocks ? per_worker : (size_t)blocks) * sizeof(uint64_t);
+}
+
+gq_status gq_global_norm(const float *const *x, int K, int64_t d, gq_norm_kind kind, float *norm_out,
+                         uint32_t *status_flags, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    GradPtrs P;
+    const gq_status st = check_global_norm_args(x, K, d, kind, norm_out, status_flags, &P);
+    if (st != GQ_OK) return st;
+    if (!workspace || workspace_bytes < gq_norm_workspace_bytes(K, d)) return GQ_ERR_WORKSPACE;
+    if (!aligned(workspace, 8)) return GQ_ERR_INVALID_ARG;
+    return launch_global_norm(P, K, d, kind, norm_out, status_flags, reinterpret_cast<uint64_t *>(workspace),
+                              (hipStream_t)hip_stream);
 }
 
 }  // extern "C"

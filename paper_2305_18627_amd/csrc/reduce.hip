@@ -1,5 +1,5 @@
 // Tree reductions of stored codes on MI355X (gfx950): Algorithm 2 for the exponential grid and the
-// in-step averaging of Section 7 for low-bit linear codes.  Contracts: include/gqsgd.h.
+// in-step averaging of the Implementation section for low-bit linear codes.  Contracts: include/gqsgd.h.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
@@ -146,7 +146,7 @@ exp_reduce_kernel(LevelCPtrs Lv, int K, int64_t d, int s, uint64_t seed, uint64_
 }
 
 // =============================================================================================
-// Section 7: low-bit linear codes averaged inside every reduce step, so that they never leave their
+// Implementation section: low-bit linear codes averaged inside every reduce step, so that they never leave their
 // b bits.  Same tree walk as exp_reduce_kernel; a node holds round((a + b) / 2), an odd sum going
 // up iff its coin is set.  The coins of up to 32 nodes are the bits of ONE Philox word per
 // coordinate (stream 2, counter word 2 = node / 32), so the kernel stays memory-bound.

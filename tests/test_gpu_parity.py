@@ -401,6 +401,56 @@ def test_fused_degenerate_inputs(rng_bits):
         assert abs(float(deq[4321].item()) - (-0.75 / K)) <= RTOL * 0.75 / K
 
 
+@pytest.mark.parametrize("rng_bits", [32, 16])
+@pytest.mark.parametrize("scheme,s,pack", [("linear", 127, "i8"), ("linear", 15, "u4s"), ("exp", 16, "i8"), ("exp", 7, "i4")])
+def test_nan_and_inf_coordinates_match_the_oracle(scheme, s, pack, rng_bits):
+    # a gradient that holds a NaN or an Inf: the norm of gq_global_norm is then unusable and EVERY code is 0, also
+    # at the NaN / Inf coordinates themselves (Inf * 0 and NaN * 0 are NaN, which must not turn into the top level);
+    # with a finite norm given by the caller a NaN coordinate rounds to 0 and an Inf coordinate to the top level
+    K, d = 4, 9_001
+    params = gq.make_params(SCHEMES[scheme], s, PACKS[pack], 0, seed=17, rng_bits=rng_bits)
+    for bad in (float("nan"), float("inf"), float("-inf")):
+        xs = gaussians(K, d, seed=3)
+        for w, pos in ((0, 0), (1, 4097), (1, 4098), (3, d - 1), (2, 777)):
+            xs[w][pos] = bad
+        xh = [host(x) for x in xs]
+        for kind in ("linf", "l2", "l2max", None):
+            if kind is None:
+                norm_t = dev_scalar(5e-3)                                 # a finite norm from the caller
+            else:
+                norm_t = dev_scalar(-1.0)
+                flags = torch.zeros(1, dtype=torch.int32, device=DEV)
+                gq.global_norm(xs, NORMS[kind], norm_t, flags)
+                assert int(flags.item()) & 1
+            nf = np.float32(norm_t.item())
+            qs = [O.quantize(xh[i], nf, SCHEMES[scheme], s, 17, i, 0, rng_bits=rng_bits) for i in range(K)]
+            want = O.aggregate(qs, SCHEMES[scheme])
+            if kind is not None:
+                assert not want.any() and not any(q.any() for q in qs)
+            elif bad != bad:
+                assert qs[1][4097] == 0 and qs[0][0] == 0
+            else:
+                assert abs(qs[1][4097]) == s
+            agg, deq, lvs, sps = run_fused(xs, norm_t, params, 0, True)
+            assert np.array_equal(host(agg)[:d].astype(np.int64), want)
+            if kind is not None:
+                assert bool((deq[:d] == 0).all())
+            lone, spone = [], []
+            for i in range(K):
+                wl, ws = O.pack(qs[i], PACKS[pack])
+                assert np.array_equal(host(lvs[i])[:wl.shape[0]], wl)
+                lv, sp = gpu_quantize(xs[i], norm_t, params, i, 0)
+                assert np.array_equal(host(lv)[:wl.shape[0]], wl)
+                if ws is not None:
+                    assert np.array_equal(host(sps[i]).view(np.uint32)[:ws.shape[0]], ws)
+                    assert np.array_equal(host(sp).view(np.uint32)[:ws.shape[0]], ws)
+                lone.append(lv); spone.append(sp)
+            dense = torch.zeros(d, dtype=torch.int32, device=DEV)
+            gq.int_aggregate(lone, spone if spone[0] is not None else None, d, params, dense)
+            torch.cuda.synchronize()
+            assert np.array_equal(host(dense).astype(np.int64), want)
+
+
 def test_fused_equals_separate_calls_and_buckets_equal_whole():
     K, d = 8, 300_007
     xs = gaussians(K, d, seed=77)
@@ -618,7 +668,7 @@ def test_exp_reduce_is_unbiased_for_the_integer_sum_on_gpu():
     assert np.all(np.abs(mean - host(exact).astype(np.float64)) <= 5.0 * sd / np.sqrt(T) + 1e-12)
 
 
-# ------------------------------------------------------------------------------------ Section 7 averaging
+# ------------------------------------------------------------------------------------ Implementation section: in-step averaging
 @pytest.mark.parametrize("K", [1, 2, 3, 4, 7, 8, 16, 32, 33, 64])
 @pytest.mark.parametrize("s,pack,d", [(7, "i4", 70_003), (7, "i4", 4098), (127, "i8", 4099), (1, "i4", 255), (15, "i8", 1021)])
 def test_avg_reduce_matches_oracle(K, s, pack, d):

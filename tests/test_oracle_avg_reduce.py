@@ -1,4 +1,4 @@
-"""Pins for the oracle's in-step averaging of low-bit linear codes (arXiv 2305.18627, Section 7:
+"""Pins for the oracle's in-step averaging of low-bit linear codes (arXiv 2305.18627, Implementation section:
 the average is taken inside every reduce step so that 4-bit codes do not overflow).  Expected values
 are exact rational means, ranges, and the headroom statement the section opens with."""
 from fractions import Fraction

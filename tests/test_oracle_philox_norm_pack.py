@@ -2,7 +2,7 @@
 
 Each expected value here comes from outside the oracle: the Philox publication's known-answer
 vectors, numpy brute force, closed forms, bytes and numbers worked out by hand, or statements the
-paper prints (arXiv 2305.18627, Section 4.2 and Section 7 on integer headroom).
+paper prints (arXiv 2305.18627, Section 4.2 and the Implementation section on integer headroom).
 """
 import os
 
@@ -166,7 +166,7 @@ def test_width_rule_statements_of_the_paper():
     # Section 4.2: with linear dithering the largest sum is n*s and one more bit holds the sign;
     # n = 16 workers and A = 4 bits cannot be satisfied for any s
     assert not any(O.check_width(O.LINEAR, s, 16, 4) for s in range(1, 16))
-    # Section 7: 4-bit linear with 4 workers leaves a single bit for the value
+    # Implementation section: 4-bit linear with 4 workers leaves a single bit for the value
     assert O.check_width(O.LINEAR, 1, 4, 4) and not O.check_width(O.LINEAR, 2, 4, 4)
     # the same rule written as the paper does, 1 + log2(s+1) + log2(n) <= A, for powers of two
     for A in (4, 8, 16, 32):

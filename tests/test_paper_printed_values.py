@@ -34,7 +34,7 @@ def test_printed_values():
     n, d, s = 16, 10 ** 6, 127
     theta_e = 1.0 / (8 * n) + math.sqrt(d) / (math.sqrt(n) * 2.0 ** (s - 1))
     close("iterations_factor_exp_example", 1.0 + n ** 1.17 * theta_e, t)
-    # Section 4.2 / Section 7 headroom statements, from the oracle's rule n*s <= 2^(A-1) - 1
+    # Section 4.2 / Implementation section headroom statements, from the oracle's rule n*s <= 2^(A-1) - 1
     close("linear_n16_A4_feasible_levels", sum(O.check_width(O.LINEAR, s_, 16, 4) for s_ in range(1, 64)), t)
     most = max(s_ for s_ in range(1, 16) if O.check_width(O.LINEAR, s_, 4, 4))
     close("linear_n4_A4_value_bits", math.log2(most + 1), t)
