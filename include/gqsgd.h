@@ -126,6 +126,18 @@ gq_status gq_global_norm(const float *const *x /* host */, int K, int64_t d, gq_
                          float *norm_out, uint32_t *status_flags,
                          void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* gq_global_norm for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same arguments without the workspace, same kernels, same
+ * bits in norm_out and status_flags.  The block partials go to a 512 KiB array that is part of the
+ * library's device image (one copy per GPU, held until the process ends), which covers every (K, d)
+ * gq_global_norm accepts; a size whose partials would not fit is answered with GQ_ERR_WORKSPACE.  The
+ * call allocates nothing and synchronises nothing.  Its first call on a device looks up the array's
+ * address (not an allocation; make that call before a capture begins); GQ_ERR_DEVICE if the runtime
+ * cannot give it.  All calls on one GPU share the array: calls that may overlap on one GPU (different
+ * streams) race and must be ordered by the caller; nothing needs clearing between calls. */
+gq_status gq_global_norm_static(const float *const *x /* host */, int K, int64_t d, gq_norm_kind kind,
+                                float *norm_out, uint32_t *status_flags, void *hip_stream);
+
 /* Algorithm 1's quantisation loop for ONE worker: y = |x|/norm, code = sign(x) * xi(y) (Definition 1, Eq. (2)).
  *   x              device fp32[d]
  *   norm           device fp32[1] (as written by gq_global_norm)

@@ -21,6 +21,7 @@ GQ_AGG_I32, GQ_AGG_I16 = 0, 1
 
 # every symbol include/gqsgd.h declares
 EXPORTS = ("gq_version", "gq_status_string", "gq_check_width", "gq_norm_workspace_bytes", "gq_global_norm",
+           "gq_global_norm_static",
            "gq_quantize", "gq_int_aggregate", "gq_dequantize", "gq_fused_quantize_aggregate", "gq_exp_reduce", "gq_avg_reduce", "gq_compact_workspace_bytes", "gq_compact",
            "gq_sparse_aggregate")
 
@@ -50,6 +51,7 @@ def _load():
         "gq_check_width": (i32, [pp, i32]),
         "gq_norm_workspace_bytes": (sz, [i32, i64]),
         "gq_global_norm": (i32, [C.POINTER(vp), i32, i64, i32, vp, vp, vp, sz, vp]),
+        "gq_global_norm_static": (i32, [C.POINTER(vp), i32, i64, i32, vp, vp, vp]),
         "gq_quantize": (i32, [vp, i64, vp, pp, u32, i64, vp, vp, vp]),
         "gq_int_aggregate": (i32, [C.POINTER(vp), C.POINTER(vp), i32, i64, pp, vp, vp]),
         "gq_dequantize": (i32, [vp, i64, vp, pp, i32, vp, vp]),
@@ -173,6 +175,14 @@ def global_norm(xs, kind, norm_out, status_flags=None, workspace=None, stream=No
                              _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
     _check(st, "gq_global_norm")
     return workspace
+
+
+def global_norm_static(xs, kind, norm_out, status_flags=None, stream=None):
+    """gq_global_norm_static: the norm with the library's own static scratch; nothing is allocated."""
+    K, d = len(xs), _need_grads(xs)
+    _need(norm_out, 4, "norm_out"); _need(status_flags, 4, "status_flags")
+    st = _lib.gq_global_norm_static(_ptr_array(xs), K, d, int(kind), _ptr(norm_out), _ptr(status_flags), _stream(stream))
+    _check(st, "gq_global_norm_static")
 
 
 def quantize(x, norm, params, worker, index_base, levels_out, signplane_out=None, stream=None):

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <mutex>
 
 #include "gqsgd.h"
 #include "gq_device.hpp"
@@ -254,6 +255,37 @@ static gq_status check_global_norm_args(const float *const *x, int K, int64_t d,
     return GQ_OK;
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Scratch of gq_global_norm_static: the block partials live in a file-scope device array instead of a
+// caller-provided workspace, for callers that cannot allocate.  65536 partials of 8 bytes cover every
+// (K, d) the library accepts (at most 2^16 tile partials, at most 64 * 1024 per-worker partials).
+// In host code the array's name is only a handle; its device address is looked up once per device.
+// ---------------------------------------------------------------------------------------------
+constexpr size_t kStaticScratchWords = (size_t)1 << 16;
+static __device__ __align__(256) uint64_t scratch[kStaticScratchWords];
+
+constexpr int kMaxDevices = 64;
+static std::mutex scratch_mutex;
+static uint64_t *scratch_ptr[kMaxDevices];       // device address of `scratch` on each device, once resolved
+
+// The address of the current device's copy of `scratch`, or nullptr if the runtime refuses.
+static uint64_t *static_scratch_of_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        scratch_ptr[dev] = reinterpret_cast<uint64_t *>(p);
+    }
+    return scratch_ptr[dev];
+}
+
 }  // namespace gq
 
 using namespace gq;
@@ -279,6 +311,19 @@ gq_status gq_global_norm(const float *const *x, int K, int64_t d, gq_norm_kind k
     if (!aligned(workspace, 8)) return GQ_ERR_INVALID_ARG;
     return launch_global_norm(P, K, d, kind, norm_out, status_flags, reinterpret_cast<uint64_t *>(workspace),
                               (hipStream_t)hip_stream);
+}
+
+gq_status gq_global_norm_static(const float *const *x, int K, int64_t d, gq_norm_kind kind, float *norm_out,
+                                uint32_t *status_flags, void *hip_stream)
+{
+    GradPtrs P;
+    const gq_status st = check_global_norm_args(x, K, d, kind, norm_out, status_flags, &P);
+    if (st != GQ_OK) return st;
+    if (gq_norm_workspace_bytes(K, d) > kStaticScratchWords * sizeof(uint64_t)) return GQ_ERR_WORKSPACE;
+    uint64_t *partial = static_scratch_of_current_device();
+    if (!partial) return GQ_ERR_DEVICE;
+    // every partial the final kernel reads is written by this call's first kernel, so nothing needs clearing
+    return launch_global_norm(P, K, d, kind, norm_out, status_flags, partial, (hipStream_t)hip_stream);
 }
 
 }  // extern "C"

@@ -104,6 +104,13 @@ def test_argument_checks_need_no_device(gq):
     assert lib.gq_global_norm(arr, 2, 16, 0, None, None, fake, 1 << 20, None) == I            # no output
     assert lib.gq_global_norm(arr, 2, 1 << 20, 0, fake, None, fake, 8, None) == gq.GQ_ERR_WORKSPACE
     assert lib.gq_global_norm(arr, 2, 1 << 20, 0, fake, None, None, 1 << 20, None) == gq.GQ_ERR_WORKSPACE
+    # gq_global_norm_static: the same checks without a workspace
+    assert lib.gq_global_norm_static(arr, 0, 16, 0, fake, None, None) == I                    # K = 0
+    assert lib.gq_global_norm_static(arr, 2, -1, 0, fake, None, None) == I                    # d < 0
+    assert lib.gq_global_norm_static(arr, 2, 16, 9, fake, None, None) == I                    # bad kind
+    assert lib.gq_global_norm_static(bad_arr, 2, 16, 0, fake, None, None) == I                # misaligned gradient
+    assert lib.gq_global_norm_static(arr, 2, 16, 0, None, None, None) == I                    # no output
+    assert lib.gq_global_norm_static(None, 2, 16, 0, fake, None, None) == I
     # gq_quantize
     q = lambda p, x=fake, d=16, base=0, lv=fake, sp=None: lib.gq_quantize(x, d, fake, C.byref(p), 0, base, lv, sp, None)
     assert q(ok, x=odd) == I and q(ok, lv=odd) == I and q(ok, base=2) == I and q(ok, base=-4) == I and q(ok, d=-1) == I
