@@ -202,3 +202,260 @@ def test_one_launch_across_two_to_the_34_coordinates():
     assert torch.equal(part, agg[lo:])
     del x, agg, part
     torch.cuda.empty_cache()
+
+
+# ------------------------------------------------------------------------------------ sparse branch at full size
+def list_window(idx, lo, hi):
+    """Positions [a, b) of the entries of the sorted device index list `idx` (int32 storage of uint32 values)
+    whose coordinate lies in [lo, hi)."""
+    wide = idx.to(torch.int64) & 0xFFFFFFFF
+    edge = torch.tensor([lo, hi], dtype=torch.int64, device=idx.device)
+    a, b = torch.searchsorted(wide, edge).tolist()
+    return a, b
+
+
+def compact_with_guard(lv, d, p, ws):
+    """gq_compact into buffers sized by a first counting call, with 8 guard entries behind them."""
+    cnt = torch.zeros(1, dtype=torch.int64, device=DEV)
+    probe_i = torch.empty(1, dtype=torch.int32, device=DEV)
+    probe_v = torch.empty(1, dtype=torch.int8, device=DEV)
+    gq.compact(lv, d, p, probe_i, probe_v, cnt, ws)
+    torch.cuda.synchronize()
+    n = int(cnt.item())
+    idx = torch.full((n + 8,), -1, dtype=torch.int32, device=DEV)
+    val = torch.full((n + 8,), 0x5A, dtype=torch.int8, device=DEV)
+    cnt.fill_(-1)
+    gq.compact(lv, d, p, idx, val, cnt, ws)
+    torch.cuda.synchronize()
+    assert int(cnt.item()) == n
+    assert bool((idx[n:] == -1).all()) and bool((val[n:] == 0x5A).all())       # nothing written past the count
+    return n, idx, val, cnt
+
+
+@pytest.mark.parametrize("kind", ["linf", "l2"])
+def test_workload_c3_sparse_branch_at_full_size(kind):
+    # Algorithm 1's sparse branch at the scored shape (d = 110e6, K = 16, linear s = 127, int8 codes): the block
+    # counts of one worker (6714 of them) take seven rounds of the scan, which smaller inputs never reach.
+    # Max norm: about 16 % of the codes are non-zero; L2 norm: about 0.05 % (the regime of Theorem 1).
+    cfg = SI.CONFIGS["c3"]
+    K, d, s = cfg["K"], cfg["d"], cfg["s"]
+    xs = SI.make_workers("c3", device=DEV)
+    nf = np.float32(torch_norm(xs, kind))
+    norm_t = torch.tensor([float(nf)], device=DEV)
+    p = gq.make_params(gq.GQ_LINEAR, s, gq.GQ_PACK_I8, gq.GQ_AGG_I32, seed=SI.QUANT_SEED)
+    lvs = [torch.empty(d, dtype=torch.uint8, device=DEV) for _ in range(K)]
+    for i in range(K):
+        gq.quantize(xs[i], norm_t, p, i, 0, lvs[i])
+    dense = torch.empty(d, dtype=torch.int32, device=DEV)
+    gq.int_aggregate(lvs, None, d, p, dense)
+    ws = torch.empty(gq.compact_workspace_bytes(d), dtype=torch.uint8, device=DEV)
+    assert gq.compact_workspace_bytes(d) == 4 * 6714
+    idxs, vals, cnts, total = [], [], [], 0
+    windows = spans(d, 33, edges=[1024 * 16384 * r for r in range(1, 7)])       # the scan's round boundaries too
+    for i in range(K):
+        n, idx, val, cnt = compact_with_guard(lvs[i], d, p, ws)
+        idxs.append(idx[:n]); vals.append(val[:n]); cnts.append(cnt); total += n
+        assert n == int(torch.count_nonzero(lvs[i]))
+        if i in (0, K - 1):
+            # the sender in full against the oracle: its own codes from the same gradient, its own list
+            q = O.quantize(host(xs[i]), nf, O.LINEAR, s, SI.QUANT_SEED, i, 0)
+            assert np.array_equal(host(lvs[i]).view(np.int8), q.astype(np.int8))
+            n_o, widx, wval = O.compact(q)
+            assert n == n_o
+            assert np.array_equal(host(idx[:n]).view(np.uint32), widx)
+            assert np.array_equal(host(val[:n]).astype(np.int32), wval)
+            del q, widx, wval
+        else:
+            # on windows: the list restricted to the window is the oracle's list of the window, and it sits at
+            # the position given by the number of non-zero codes before the window
+            for lo, hi in windows:
+                q = O.quantize(host(xs[i][lo:hi]), nf, O.LINEAR, s, SI.QUANT_SEED, i, lo)
+                n_w, widx, wval = O.compact(q)
+                a, b = list_window(idx[:n], lo, hi)
+                assert b - a == n_w and a == int(torch.count_nonzero(lvs[i][:lo])), (i, lo)
+                assert np.array_equal(host(idx[a:b]).view(np.uint32).astype(np.int64), widx.astype(np.int64) + lo)
+                assert np.array_equal(host(val[a:b]).astype(np.int32), wval)
+    frac = total / (float(K) * d)
+    assert (0.10 < frac < 0.25) if kind == "linf" else (0.0002 < frac < 0.002)      # about 16 % and 0.05 %
+    if kind == "l2":
+        assert total <= 1.2 * (s * s + s * np.sqrt(float(K) * d))               # the bound Eq. (2) implies
+    # the receiver: the K lists add up to the dense integer sum over every coordinate, and to the oracle's on windows
+    agg = torch.full((d + 8,), 0x5A5A, dtype=torch.int32, device=DEV)
+    gq.sparse_aggregate(idxs, vals, cnts, d, p, agg)
+    torch.cuda.synchronize()
+    assert torch.equal(agg[:d], dense) and bool((agg[d:] == 0x5A5A).all())
+    for lo, hi in windows:
+        want = O.quantize_aggregate([host(x[lo:hi]) for x in xs], nf, O.LINEAR, s, SI.QUANT_SEED, lo)
+        assert np.array_equal(host(agg[lo:hi]).astype(np.int64), want), lo
+        # and the oracle's own receiver on the window's part of the lists
+        wi, wv = [], []
+        for i in range(K):
+            a, b = list_window(idxs[i], lo, hi)
+            wi.append((host(idxs[i][a:b]).view(np.uint32).astype(np.int64) - lo).astype(np.uint32))
+            wv.append(host(vals[i][a:b]).astype(np.int32))
+        assert np.array_equal(O.sparse_aggregate(wi, wv, hi - lo, O.LINEAR), want)
+
+
+def test_sparse_branch_with_32_bit_indices_up_to_the_limit():
+    # d = 2^32 - 1, the largest gradient the sparse branch takes: coordinate indices use all 32 bits, the scan
+    # of 262144 block counts runs 256 rounds.  Two mostly-zero code vectors are built from seeded positions,
+    # so the expected lists are the construction itself (sorted positions and their codes); the oracle's
+    # compaction and receiver are run on windows of the same vectors.
+    torch.cuda.empty_cache()
+    d = (1 << 32) - 1
+    free, _ = torch.cuda.mem_get_info()
+    if free < 60 * (1 << 30):
+        pytest.skip("needs 60 GB of free device memory")
+    assert gq.compact_workspace_bytes(d) == 4 * 262144 and gq.compact_workspace_bytes(d + 1) == 0
+    rng = np.random.default_rng(2032)
+    half = 1 << 31
+    special = np.array([0, 1, 15, 16, 16383, 16384, 65535, 65536, half - 1, half, half + 1, d - 2, d - 1,
+                        16384 * 1024 - 1, 16384 * 1024, 255 * 16384 * 1024 + 5], dtype=np.int64)
+    runs = np.concatenate([np.arange(half - 30_000, half + 30_000), np.arange(d - 40_000, d),
+                           np.arange(7 * 16384 * 1024 - 5000, 7 * 16384 * 1024 + 5000)])
+    p = gq.make_params(gq.GQ_LINEAR, 127, gq.GQ_PACK_I8, gq.GQ_AGG_I32, seed=0)
+    ws = torch.empty(gq.compact_workspace_bytes(d), dtype=torch.uint8, device=DEV)
+    lvs, lists, pos_all, val_all = [], [], [], []
+    for w in range(2):
+        pos = np.unique(np.concatenate([rng.integers(0, d, 3_000_000), special, runs if w == 0 else runs[::3]]))
+        val = rng.integers(1, 128, pos.shape[0]).astype(np.int8) * rng.choice(np.array([-1, 1], np.int8), pos.shape[0])
+        lv = torch.zeros(d, dtype=torch.int8, device=DEV)
+        lv[torch.from_numpy(pos).to(DEV)] = torch.from_numpy(val).to(DEV)
+        n, idx, vv, cnt = compact_with_guard(lv, d, p, ws)
+        assert n == pos.shape[0]
+        assert np.array_equal(host(idx[:n]).view(np.uint32).astype(np.int64), pos)
+        assert np.array_equal(host(vv[:n]), val)
+        lvs.append(lv); lists.append((idx[:n], vv[:n], cnt)); pos_all.append(pos); val_all.append(val)
+        # the oracle's compaction on windows of the same vector
+        for lo, hi in [(0, 1 << 20), (half - (1 << 19), half + (1 << 19)), (d - (1 << 20), d),
+                       (255 * 16384 * 1024 - 4096, 255 * 16384 * 1024 + 4096)]:
+            n_w, widx, wval = O.compact(host(lv[lo:hi]).astype(np.int32))
+            a, b = np.searchsorted(pos, [lo, hi])
+            assert n_w == b - a
+            assert np.array_equal(host(idx[a:b]).view(np.uint32).astype(np.int64), widx.astype(np.int64) + lo)
+            assert np.array_equal(host(vv[a:b]).astype(np.int32), wval)
+    # a short buffer: the true count and the first entries
+    short_i = torch.full((1000 + 8,), -1, dtype=torch.int32, device=DEV)
+    short_v = torch.full((1000 + 8,), 0x5A, dtype=torch.int8, device=DEV)
+    cnt = torch.zeros(1, dtype=torch.int64, device=DEV)
+    gq.compact(lvs[0], d, p, short_i[:1000], short_v[:1000], cnt, ws)
+    torch.cuda.synchronize()
+    assert int(cnt.item()) == pos_all[0].shape[0] and torch.equal(short_i[:1000], lists[0][0][:1000])
+    assert bool((short_i[1000:] == -1).all()) and bool((short_v[1000:] == 0x5A).all())
+    # the receiver: both lists into the dense sum; against the dense path over every coordinate, against the
+    # construction (scatter-add of the positions), and against the oracle's receiver on windows
+    agg = torch.empty(d, dtype=torch.int32, device=DEV)
+    gq.sparse_aggregate([l[0] for l in lists], [l[1] for l in lists], [l[2] for l in lists], d, p, agg)
+    dense = torch.empty(d, dtype=torch.int32, device=DEV)
+    gq.int_aggregate([lv.view(torch.uint8) for lv in lvs], None, d, p, dense)
+    torch.cuda.synchronize()
+    assert torch.equal(agg, dense)
+    del dense
+    built = torch.zeros(d, dtype=torch.int32, device=DEV)
+    for pos, val in zip(pos_all, val_all):
+        built.index_add_(0, torch.from_numpy(pos).to(DEV), torch.from_numpy(val.astype(np.int32)).to(DEV))
+    assert torch.equal(agg, built)
+    del built
+    for lo, hi in [(0, 1 << 16), (half - (1 << 15), half + (1 << 15)), (d - (1 << 16), d)]:
+        wi, wv = [], []
+        for pos, val in zip(pos_all, val_all):
+            a, b = np.searchsorted(pos, [lo, hi])
+            wi.append((pos[a:b] - lo).astype(np.uint32)); wv.append(val[a:b].astype(np.int32))
+        assert np.array_equal(O.sparse_aggregate(wi, wv, hi - lo, O.LINEAR), host(agg[lo:hi]).astype(np.int64))
+    del agg, lvs, lists
+    torch.cuda.empty_cache()
+
+
+# ------------------------------------------------------------------------------------ tree reductions at full size
+def test_workload_c4_algorithm_2_at_full_size():
+    # Algorithm 2 (the paper's reduce function for exponential dithering) over K = 32 int8 code vectors of
+    # d = 350e6 coordinates, the shape of workload c4: reduced (sign, e) codes bit-exact on windows, the mean they
+    # stand for to 1e-5, and properties that hold everywhere
+    cfg = SI.CONFIGS["c4"]
+    K, d, s = cfg["K"], cfg["d"], cfg["s"]
+    xs = SI.make_workers("c4", device=DEV)
+    nf = np.float32(torch_norm(xs, "linf"))
+    norm_t = torch.tensor([float(nf)], device=DEV)
+    p = gq.make_params(gq.GQ_EXP, s, gq.GQ_PACK_I8, gq.GQ_AGG_I32, seed=SI.QUANT_SEED)
+    lvs = [torch.empty(d, dtype=torch.uint8, device=DEV) for _ in range(K)]
+    for i in range(K):
+        gq.quantize(xs[i], norm_t, p, i, 0, lvs[i])
+    red = torch.empty(d, dtype=torch.int8, device=DEV)
+    deq = torch.empty(d, device=DEV)
+    gq.exp_reduce(lvs, d, p, 0, norm_t, red, deq)
+    torch.cuda.synchronize()
+    for lo, hi in spans(d, 44):
+        qs = [O.quantize(host(xs[i][lo:hi]), nf, O.EXP, s, SI.QUANT_SEED, i, lo) for i in range(K)]
+        for i in (0, 17, K - 1):
+            assert np.array_equal(host(lvs[i][lo:hi]).view(np.int8), qs[i].astype(np.int8))
+        want = O.exp_tree_reduce(qs, s, SI.QUANT_SEED, lo)
+        assert np.array_equal(host(red[lo:hi]).astype(np.int32), want), lo
+        wd = O.exp_reduce_dequantize(want, float(nf), K)
+        gd = host(deq[lo:hi]).astype(np.float64)
+        assert np.all(np.abs(gd - wd) <= RTOL * np.abs(wd)) and np.all(gd[want == 0] == 0.0)
+    # everywhere: exponents stay inside the prescaled range 1 .. s + log2(n'), and a coordinate whose codes
+    # are all zero reduces to zero
+    assert int(red.abs().max()) <= s + 5
+    anyone = torch.zeros(d, dtype=torch.bool, device=DEV)
+    for lv in lvs:
+        anyone |= lv != 0
+    assert not bool((red[~anyone] != 0).any())
+    # unbiased for the exact integer sum (Section 4.3): summed over all coordinates along the sign of the exact
+    # mean, the error stays within 6 standard deviations.  A node's second moment is at most 9/8 of its exact
+    # sum's square, so by induction over the 5 tree levels Var(result_j) <= (9/8)^5 (sum_i |value_ij|)^2.
+    agg = torch.empty(d, dtype=torch.int32, device=DEV)
+    gq.int_aggregate(lvs, None, d, p, agg)
+    exact = torch.empty(d, device=DEV)
+    gq.dequantize(agg, d, norm_t, p, K, exact)
+    absval = torch.zeros(d, device=DEV)
+    for lv in lvs:
+        k = lv.view(torch.int8).abs()
+        absval += torch.where(k > 0, torch.exp2(k.float() - 1.0), torch.zeros((), device=DEV))
+    absmean = absval.double() * (float(nf) / (K * 2.0 ** (s - 1)))
+    torch.cuda.synchronize()
+    diff = float(((deq.double() - exact.double()) * torch.sign(exact).double()).sum())
+    assert abs(diff) <= 6.0 * np.sqrt((9.0 / 8.0) ** 5 * float((absmean * absmean).sum()))
+
+
+@pytest.mark.parametrize("pack", ["i8", "i4"])
+def test_workload_c3_in_step_averaging_at_full_size(pack):
+    # the Implementation section's in-step averaging over K = 16 code vectors of d = 110e6 coordinates (workload c3's
+    # shape): int8 codes with s = 127, and packed 4-bit codes with s = 7
+    cfg = SI.CONFIGS["c3"]
+    K, d = cfg["K"], cfg["d"]
+    s = 127 if pack == "i8" else 7
+    fmt = gq.GQ_PACK_I8 if pack == "i8" else gq.GQ_PACK_I4
+    xs = SI.make_workers("c3", device=DEV)
+    nf = np.float32(torch_norm(xs, "linf"))
+    norm_t = torch.tensor([float(nf)], device=DEV)
+    p = gq.make_params(gq.GQ_LINEAR, s, fmt, gq.GQ_AGG_I32, seed=SI.QUANT_SEED)
+    nb = gq.levels_nbytes(d, fmt)
+    lvs = [torch.empty(nb, dtype=torch.uint8, device=DEV) for _ in range(K)]
+    for i in range(K):
+        gq.quantize(xs[i], norm_t, p, i, 0, lvs[i])
+    red = torch.empty(nb, dtype=torch.uint8, device=DEV)
+    deq = torch.empty(d, device=DEV)
+    gq.avg_reduce(lvs, d, p, 0, norm_t, red, deq)
+    torch.cuda.synchronize()
+    per = 1 if pack == "i8" else 2
+    for lo, hi in spans(d, 55):
+        qs = [O.quantize(host(xs[i][lo:hi]), nf, O.LINEAR, s, SI.QUANT_SEED, i, lo) for i in range(K)]
+        want = O.avg_tree_reduce(qs, SI.QUANT_SEED, lo)
+        wl, _ = O.pack(want, O.PACK_I8 if pack == "i8" else O.PACK_I4)
+        assert np.array_equal(host(red[lo // per:(hi + per - 1) // per]), wl), lo
+        wd = O.avg_reduce_dequantize(want, float(nf), s, K)
+        gd = host(deq[lo:hi]).astype(np.float64)
+        assert np.all(np.abs(gd - wd) <= RTOL * np.abs(wd)) and np.all(gd[want == 0] == 0.0)
+    # everywhere: the averaged code never leaves the range of the inputs' codes, and, summed over all coordinates
+    # along the sign of the exact mean, the result agrees with the exact mean of the codes within 6 standard
+    # deviations of the coin noise (a node adds at most 1/4 of variance, halved in weight at every level above it:
+    # less than 1/2 at the root, in units of one code)
+    agg = torch.empty(d, dtype=torch.int32, device=DEV)
+    gq.int_aggregate(lvs, None, d, p, agg)
+    exact = torch.empty(d, device=DEV)
+    gq.dequantize(agg, d, norm_t, p, K, exact)
+    torch.cuda.synchronize()
+    unit = float(nf) / s
+    assert float(deq.abs().max()) <= float(nf) * (1 + 1e-6)
+    diff = float(((deq.double() - exact.double()) * torch.sign(exact).double()).sum())
+    assert abs(diff) <= 6.0 * unit * np.sqrt(d * 0.5)
