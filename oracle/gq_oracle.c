@@ -288,17 +288,25 @@ int64_t gqo_max_aggregate(int scheme, int s, int K)
     return (int64_t)K * ((int64_t)1 << (s - 1));
 }
 
+/* Largest value of a signed integer of `bits` bits, 2^(bits-1) - 1 (Section 4.2 counts one bit for the sign);
+ * widths of 64 and more are limited by the int64 the sums are held in here. */
+static int64_t width_limit(int bits)
+{
+    if (bits < 1) return -1;
+    if (bits >= 64) return INT64_MAX;
+    return (int64_t)(((uint64_t)1 << (bits - 1)) - 1u);
+}
+
 /* 1 if a signed integer of `bits` bits always holds the sum, else 0. */
 int gqo_check_width(int scheme, int s, int K, int bits)
 {
-    int64_t lim = ((int64_t)1 << (bits - 1)) - 1;
-    return gqo_max_aggregate(scheme, s, K) <= lim;
+    return gqo_max_aggregate(scheme, s, K) <= width_limit(bits);
 }
 
 /* 1 if every A_j fits a signed integer of `bits` bits. */
 int gqo_fits_width(const int64_t *A, int64_t d, int bits)
 {
-    int64_t lim = ((int64_t)1 << (bits - 1)) - 1;
+    int64_t lim = width_limit(bits);
     for (int64_t j = 0; j < d; j++) if (A[j] > lim || A[j] < -lim - 1) return 0;
     return 1;
 }
