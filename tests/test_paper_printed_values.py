@@ -14,7 +14,7 @@ def printed():
         if not line.strip() or line.startswith("#"):
             continue
         key, value, tol, where = [t.strip() for t in line.split("|", 3)]
-        assert where.startswith("Section"), "every value carries its citation"
+        assert where.startswith(("Section", "Implementation section")), "every value carries its citation"
         out[key] = (float(value), float(tol))
     return out
 
