@@ -43,6 +43,15 @@ def parse():
                     help="after the timed steps, run three plain 1 GiB device copies (a kernel of known "
                          "traffic for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--per-bucket-norm", action="store_true",
+                    help="bucketed workloads (c5): every bucket under its OWN norm (gq_bucketed_quantize_aggregate), "
+                         "timed with the serial schedule and with the next bucket's norm on a second stream; "
+                         "both step times are reported under \"per_bucket_norm\"")
+    ap.add_argument("--two-streams", action="store_true",
+                    help="with --per-bucket-norm: the headline ms_per_step is the two-stream schedule (default: serial)")
+    ap.add_argument("--no-window-ab", action="store_true",
+                    help="skip the interleaved timing of the fused call with its write windows forced off and on")
+    ap.add_argument("--ab-rounds", type=int, default=15, help="rounds of the write-window A/B (each times off, then on)")
     ap.add_argument("--graph", action="store_true",
                     help="also capture the step in a HIP graph and time its replays (reported as graph_replay_ms_per_step)")
     return ap.parse_args()
@@ -56,7 +65,10 @@ def cpu_baseline(xs, nf, scheme, s, seed, sample, bytes_per_coord):
     d = xs[0].numel()
     sample = min(sample, d)
     host = [x[:sample].cpu().numpy() for x in xs]
-    threads = max(1, min(16, os.cpu_count() or 1))
+    # every host core this job may use: a GPU machine gives a one-GPU job a share of 16 cores whatever
+    # os.cpu_count() shows there (OMP_NUM_THREADS carries that share)
+    share = int(os.environ.get("OMP_NUM_THREADS", "0") or 0)
+    threads = max(1, min(os.cpu_count() or 1, share if share > 0 else 16))
     per = (sample + threads - 1) // threads
     per = (per + 3) & ~3
     cuts = [(lo, min(sample, lo + per)) for lo in range(0, sample, per)]
@@ -210,7 +222,28 @@ def main():
     if bucket:      # bucketed workload: per bucket one fused quantize+aggregate+dequantize call, offsets passed on
         views = [(lo, [x[lo:min(d, lo + bucket)] for x in xs], out[lo:min(d, lo + bucket)]) for lo in range(0, d, bucket)]
 
+    per_bucket = bool(bucket) and args.per_bucket_norm
+    if args.per_bucket_norm and not bucket:
+        print("bench.py: --per-bucket-norm needs a bucketed workload (c5)", file=sys.stderr)
+        sys.exit(2)
+    side = torch.cuda.Stream() if per_bucket else None          # default priority, like the main stream
+    if per_bucket:
+        nbk = SI.num_buckets(d, bucket)
+        norms_b = torch.zeros(nbk, device=dev)
+        flags_b = torch.zeros(nbk, dtype=torch.int32, device=dev)
+        ws_b = torch.empty(gq.bucketed_workspace_bytes(K, d, bucket), dtype=torch.uint8, device=dev)
+
+    def bucketed_step(two_streams):
+        gq.bucketed_quantize_aggregate(xs, bucket, kind, params, norms_b, flags_b, None, out, ws_b,
+                                       side_stream=side if two_streams else None)
+
     def step(ev=None):
+        if per_bucket:
+            # norm and fused calls alternate bucket by bucket inside one library call: only the whole step is timed
+            if ev: ev[0].record(); ev[1].record()
+            bucketed_step(args.two_streams)
+            if ev: ev[2].record(); ev[3].record()
+            return
         if ev: ev[0].record()
         gq.global_norm(xs, kind, norm, flags, ws)
         if ev: ev[1].record()
@@ -243,18 +276,63 @@ def main():
     b_norm = 4.0 * K * d
     b_fused = (4.0 * K + 4.0) * d
     b_deq = 0.0 if bucket else 8.0 * d
-    fused_ms = float(np.mean(t_fused))
+    fused_ms = float(np.mean(t_fused)) if not per_bucket else ms_per_step
     fused_gbps = b_fused / fused_ms * 1e-6
     step_gbps = (b_norm + b_fused + b_deq) / ms_per_step * 1e-6
 
-    traffic = valu_busy = None
+    def time_calls(fn, n):
+        ts = []
+        for _ in range(n):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(); fn(); b.record(); b.synchronize()
+            ts.append(a.elapsed_time(b))
+        return ts
+
+    schedules = None
+    if per_bucket:
+        # both schedules of the per-bucket-norm step, interleaved in this warmed-up process
+        ser, two = [], []
+        for _ in range(max(3, args.steps // 2)):
+            ser += time_calls(lambda: bucketed_step(False), 1)
+            two += time_calls(lambda: bucketed_step(True), 1)
+        schedules = {"serial_ms": float(np.mean(ser)), "two_streams_ms": float(np.mean(two)),
+                     "serial_min_ms": float(np.min(ser)), "two_streams_min_ms": float(np.min(two)),
+                     "headline": "two_streams" if args.two_streams else "serial", "buckets": nbk,
+                     "algorithmic_bytes": (8.0 * K + 4.0) * d,
+                     "note": "norm of bucket b+1 on a second stream beside the fused call of bucket b; identical outputs"}
+
+    windows_ab = None
+    if not bucket and not args.no_window_ab:
+        # the fused call with its write windows forced off and forced on, interleaved, same buffers, same process
+        p_off = gq.make_params(scheme, s, gq.GQ_PACK_I8, gq.GQ_AGG_I32, seed=SI.QUANT_SEED, flags=gq.GQ_FLAG_WRITE_WINDOWS_OFF)
+        p_on = gq.make_params(scheme, s, gq.GQ_PACK_I8, gq.GQ_AGG_I32, seed=SI.QUANT_SEED, flags=gq.GQ_FLAG_WRITE_WINDOWS_ON)
+        t_off, t_on = [], []
+        for _ in range(args.ab_rounds):
+            t_off += time_calls(lambda: gq.fused_quantize_aggregate(xs, norm, p_off, 0, agg, None), 1)
+            t_on += time_calls(lambda: gq.fused_quantize_aggregate(xs, norm, p_on, 0, agg, None), 1)
+        by_policy = K >= 8 and float(K) * d >= 2.5e8
+        windows_ab = {"windows_off_ms": float(np.mean(t_off)), "windows_on_ms": float(np.mean(t_on)),
+                      "windows_off_median_ms": float(np.median(t_off)), "windows_on_median_ms": float(np.median(t_on)),
+                      "rounds": args.ab_rounds,
+                      "headline_used": "windows_on" if by_policy else "windows_off",
+                      "note": "interleaved off/on calls after the timed steps; the headline is the library's default policy"}
+
+    traffic = valu_busy = traffic_note = None
     if args.workload == "c3" and os.path.exists(TRAFFIC_FILE):
+        # rocprofv3 cannot run inside this process: the HBM byte counts were profiled offline, and the file says on
+        # which library version; figures of another version are not reported
         try:
             prof = json.load(open(TRAFFIC_FILE))
-            traffic = prof.get("hbm_bytes_per_launch")
-            valu_busy = prof.get("valu_busy_frac")          # from the SQ counters of the same command
-        except Exception:
+            if prof.get("library_version") == gq.version():
+                traffic = prof.get("hbm_bytes_per_launch")
+                valu_busy = prof.get("valu_busy_frac")          # from the SQ counters of the same command
+                traffic_note = "profiled offline with rocprofv3 on library version %d (%s)" % (gq.version(), prof.get("source"))
+            else:
+                traffic_note = ("profiles/ holds counters of library version %s, this is %d: not reported"
+                                % (prof.get("library_version"), gq.version()))
+        except Exception as e:
             traffic = valu_busy = None
+            traffic_note = "traffic figures unreadable: %r" % (e,)
 
     line = {
         "metric": ("fused quantize+aggregate GB/s and % of HBM peak, d=110M K=16 fp32" if args.workload == "c3" else
@@ -272,15 +350,30 @@ def main():
                      "frac": fused_gbps / HBM_PEAK_GBPS, "traffic": traffic,
                      "kernel": "quantize_aggregate_kernel", "algorithmic_bytes_per_launch": b_fused,
                      "avg_ms": fused_ms, "median_ms": float(np.median(t_fused)), "min_ms": float(np.min(t_fused)),
-                     "valu_busy_frac_profiled": valu_busy},
+                     "valu_busy_frac_profiled": valu_busy, "traffic_note": traffic_note},
         "step_GBps": step_gbps, "step_algorithmic_bytes": b_norm + b_fused + b_deq, "wall_ms_per_step": wall_ms / args.steps,
         "calls_ms": {"global_norm": float(np.mean(t_norm)), "fused_quantize_aggregate": fused_ms,
                      "dequantize": float(np.mean(t_deq))},
         "buckets": len(views) if views else None,
-        "calls_GBps": {"global_norm": b_norm / float(np.mean(t_norm)) * 1e-6, "fused_quantize_aggregate": fused_gbps,
-                       "dequantize": (b_deq / float(np.mean(t_deq)) * 1e-6) if b_deq else None},
+        "calls_GBps": {"global_norm": b_norm / max(float(np.mean(t_norm)), 1e-9) * 1e-6, "fused_quantize_aggregate": fused_gbps,
+                       "dequantize": (b_deq / max(float(np.mean(t_deq)), 1e-9) * 1e-6) if b_deq else None},
         "norm_flags": int(flags.item()),
     }
+    if windows_ab:
+        line["roofline"].update(windows_ab)
+    if schedules:
+        line["per_bucket_norm"] = schedules
+        line["config"]["step"] = "per bucket: global_norm of the bucket -> fused quantize+aggregate+dequantize (%s schedule)" % schedules["headline"]
+        line["calls_ms"] = {"bucketed_quantize_aggregate": ms_per_step}
+        line["calls_GBps"] = {"bucketed_quantize_aggregate": schedules["algorithmic_bytes"] / ms_per_step * 1e-6}
+        line["value"] = line["calls_GBps"]["bucketed_quantize_aggregate"]
+        line["metric"] = "per-bucket norm + fused quantize+aggregate+dequantize GB/s, workload %s (d=%d K=%d fp32)" % (args.workload, d, K)
+        line["pct_of_hbm_peak"] = 100.0 * line["value"] / HBM_PEAK_GBPS
+        line["roofline"] = {"bound": "hbm", "achieved": line["value"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                            "frac": line["value"] / HBM_PEAK_GBPS, "traffic": None,
+                            "kernel": "norm_tile_kernel + quantize_aggregate_kernel per bucket",
+                            "algorithmic_bytes_per_launch": schedules["algorithmic_bytes"]}
+        line["norm_flags"] = int(flags_b.max().item())
     if 4.0 * K * d <= 256e6:
         line["config"]["note"] = ("the inputs (%.0f MB) fit the 256 MB last-level cache and every call is launch-bound: "
                                   "not an HBM figure" % (4.0 * K * d / 1e6))

@@ -96,9 +96,19 @@ typedef struct {
     int32_t pack;     /* gq_pack: format of level buffers (ignored where none is touched) */
     int32_t agg;      /* gq_agg: format of the integer sum (ignored where none is touched) */
     int32_t rng_bits; /* random bits per coordinate of the quantisation draw: 32 (0 reads as 32) or 16 */
-    int32_t reserved; /* set to 0                                                         */
+    int32_t flags;    /* 0, or one of the GQ_FLAG_* bits below; any other bit: GQ_ERR_INVALID_ARG   */
     uint64_t seed;    /* Philox key                                                       */
 } gq_params;
+
+/* gq_params.flags.  The fused call stores its sums either as each wave finishes or, in large launches, only
+ * inside short chip-wide time windows (all waves watch the same 100 MHz counter), which separates the
+ * write bursts from the read stream in HBM.  The windows change timing only, never a result.  By default the
+ * library uses them where they were measured to pay (K >= 8 and K * d >= 2.5e8, no codes stored).  The two
+ * bits override that policy: OFF never waits, ON waits in every launch that stores no codes.  Both
+ * bits at once: GQ_ERR_INVALID_ARG.  Every call other than gq_fused_quantize_aggregate (and the bucketed
+ * schedule built on it) ignores them. */
+#define GQ_FLAG_WRITE_WINDOWS_OFF 1
+#define GQ_FLAG_WRITE_WINDOWS_ON 2
 
 /* Library version (major * 1000 + minor). */
 int gq_version(void);
@@ -178,6 +188,31 @@ gq_status gq_fused_quantize_aggregate(const float *const *x /* host */, int K, i
                                       void *agg_out, float *dequant_out,
                                       void *const *levels_out /* host */, uint32_t *const *signplanes_out /* host */,
                                       void *hip_stream);
+
+/* The per-bucket schedule: what a communication hook that is called once per gradient bucket runs
+ * (Implementation section), with the pipelining the paper leaves open (Algorithm 1's remark that the norm
+ * exchange can be hidden behind the preceding round; Evaluation section, "Limitations").  The gradient
+ * is cut into buckets of `bucket` coordinates (a multiple of 8; the last one may be shorter); bucket b gets
+ * its OWN norm, norms_out[b] = gq_global_norm of the K slices, and is quantised and summed with it by
+ * gq_fused_quantize_aggregate with index_base = b * bucket -- the same kernels, so the same bits as those
+ * two calls made bucket by bucket.
+ *   norms_out      device fp32[ceil(d / bucket)]; status_flags device uint32[ceil(d / bucket)] or NULL
+ *   agg_out        device int32[d] / int16[d] (p->agg) or NULL; dequant_out device fp32[d] or NULL (one is needed):
+ *                  slice b holds the sum / the mean of bucket b under norm b
+ *   workspace      device scratch of at least gq_bucketed_workspace_bytes(K, d, bucket) bytes
+ *   hip_stream     carries every fused call (and every norm if side_stream is NULL: the serial schedule)
+ *   side_stream    a second hipStream_t of the same priority, or NULL.  If given, the norm of bucket b + 1 runs on
+ *                  it beside the fused call of bucket b; the call forks it from hip_stream on entry and joins
+ *                  it back before returning (HIP events created and destroyed inside the call), so the caller
+ *                  orders nothing itself and work enqueued on hip_stream afterwards sees every result.
+ * Results do not depend on the schedule.  On one GPU both kernels draw on the same HBM, so the second
+ * stream hides nothing (measured: it is slower); it is there for callers whose norm step has something to
+ * hide behind.  Errors as in the two calls; at most 65536 buckets. */
+size_t gq_bucketed_workspace_bytes(int K, int64_t d, int64_t bucket);
+gq_status gq_bucketed_quantize_aggregate(const float *const *x /* host */, int K, int64_t d, int64_t bucket,
+                                         gq_norm_kind kind, const gq_params *p /* host */, float *norms_out,
+                                         uint32_t *status_flags, void *agg_out, float *dequant_out,
+                                         void *workspace, size_t workspace_bytes, void *hip_stream, void *side_stream);
 
 /* Algorithm 2 (Section 4.3): the paper's own aggregation for the exponential grid, kept beside the
  * exact integer sum of gq_int_aggregate.  The K workers' codes (written by gq_quantize with GQ_EXP and

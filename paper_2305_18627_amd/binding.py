@@ -18,17 +18,18 @@ GQ_NORM_LINF, GQ_NORM_L2, GQ_NORM_L2_MAX = 0, 1, 2
 GQ_LINEAR, GQ_EXP = 0, 1
 GQ_PACK_I8, GQ_PACK_I4, GQ_PACK_U8_SIGNPLANE, GQ_PACK_U4_SIGNPLANE = 0, 1, 2, 3
 GQ_AGG_I32, GQ_AGG_I16 = 0, 1
+GQ_FLAG_WRITE_WINDOWS_OFF, GQ_FLAG_WRITE_WINDOWS_ON = 1, 2
 
 # every symbol include/gqsgd.h declares
 EXPORTS = ("gq_version", "gq_status_string", "gq_check_width", "gq_norm_workspace_bytes", "gq_global_norm",
-           "gq_global_norm_static",
+           "gq_global_norm_static", "gq_bucketed_workspace_bytes", "gq_bucketed_quantize_aggregate",
            "gq_quantize", "gq_int_aggregate", "gq_dequantize", "gq_fused_quantize_aggregate", "gq_exp_reduce", "gq_avg_reduce", "gq_compact_workspace_bytes", "gq_compact",
            "gq_sparse_aggregate")
 
 
 class gq_params(C.Structure):
     _fields_ = [("scheme", C.c_int32), ("s", C.c_int32), ("pack", C.c_int32), ("agg", C.c_int32),
-                ("rng_bits", C.c_int32), ("reserved", C.c_int32), ("seed", C.c_uint64)]
+                ("rng_bits", C.c_int32), ("flags", C.c_int32), ("seed", C.c_uint64)]
 
 
 class GQError(RuntimeError):
@@ -55,6 +56,8 @@ def _load():
         "gq_quantize": (i32, [vp, i64, vp, pp, u32, i64, vp, vp, vp]),
         "gq_int_aggregate": (i32, [C.POINTER(vp), C.POINTER(vp), i32, i64, pp, vp, vp]),
         "gq_dequantize": (i32, [vp, i64, vp, pp, i32, vp, vp]),
+        "gq_bucketed_workspace_bytes": (sz, [i32, i64, i64]),
+        "gq_bucketed_quantize_aggregate": (i32, [C.POINTER(vp), i32, i64, i64, i32, pp, vp, vp, vp, vp, vp, sz, vp, vp]),
         "gq_exp_reduce": (i32, [C.POINTER(vp), i32, i64, pp, i64, vp, vp, vp, vp]),
         "gq_avg_reduce": (i32, [C.POINTER(vp), i32, i64, pp, i64, vp, vp, vp, vp]),
         "gq_compact_workspace_bytes": (sz, [i64]),
@@ -136,8 +139,8 @@ def _need_levels(levels, signplanes, d, params, what="levels"):
             _need(t, 4 * signplane_nwords(d), "sign plane")
 
 
-def make_params(scheme, s, pack=GQ_PACK_I8, agg=GQ_AGG_I32, seed=0, rng_bits=32):
-    return gq_params(int(scheme), int(s), int(pack), int(agg), int(rng_bits), 0, int(seed))
+def make_params(scheme, s, pack=GQ_PACK_I8, agg=GQ_AGG_I32, seed=0, rng_bits=32, flags=0):
+    return gq_params(int(scheme), int(s), int(pack), int(agg), int(rng_bits), int(flags), int(seed))
 
 
 def levels_nbytes(d, pack):
@@ -217,6 +220,28 @@ def fused_quantize_aggregate(xs, norm, params, index_base=0, agg_out=None, dequa
                                           _ptr(agg_out), _ptr(dequant_out), _ptr_array(levels_out),
                                           _ptr_array(signplanes_out), _stream(stream))
     _check(st, "gq_fused_quantize_aggregate")
+
+
+def bucketed_workspace_bytes(K, d, bucket):
+    return int(_lib.gq_bucketed_workspace_bytes(int(K), int(d), int(bucket)))
+
+
+def bucketed_quantize_aggregate(xs, bucket, kind, params, norms_out, status_flags=None, agg_out=None, dequant_out=None,
+                                workspace=None, stream=None, side_stream=None):
+    """gq_bucketed_quantize_aggregate: per bucket its own norm and fused quantize+aggregate; with side_stream the
+    norm of the next bucket runs beside the fused call of the current one.  Returns the workspace used."""
+    K, d = len(xs), _need_grads(xs)
+    nb = (d + int(bucket) - 1) // int(bucket) if bucket > 0 else 0
+    _need(norms_out, 4 * nb, "norms_out"); _need(status_flags, 4 * nb, "status_flags")
+    _need(agg_out, _agg_bytes(params) * d, "agg_out"); _need(dequant_out, 4 * d, "dequant_out")
+    if workspace is None:
+        workspace = torch.empty(max(bucketed_workspace_bytes(K, d, bucket), 8), dtype=torch.uint8, device=norms_out.device)
+    side = _stream(side_stream) if side_stream is not None else C.c_void_p(None)
+    st = _lib.gq_bucketed_quantize_aggregate(_ptr_array(xs), K, d, int(bucket), int(kind), C.byref(params), _ptr(norms_out),
+                                             _ptr(status_flags), _ptr(agg_out), _ptr(dequant_out), _ptr(workspace),
+                                             workspace.numel() * workspace.element_size(), _stream(stream), side)
+    _check(st, "gq_bucketed_quantize_aggregate")
+    return workspace
 
 
 def exp_reduce(levels, d, params, index_base=0, norm=None, reduced_out=None, dequant_out=None, stream=None):

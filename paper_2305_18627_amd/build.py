@@ -7,7 +7,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgqsgd.so")
 SOURCES = [os.path.join(CSRC, f) for f in ("common.hip", "norm.hip", "quantize.hip", "aggregate.hip", "reduce.hip",
-                                           "sparse.hip")]
+                                           "sparse.hip", "pipeline.hip")]
 HEADERS = [os.path.join(CSRC, "gq_device.hpp"), os.path.join(CSRC, "gq_host.hpp"),
            os.path.join(ROOT, "include", "gqsgd.h")]
 

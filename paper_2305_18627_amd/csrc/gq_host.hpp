@@ -25,6 +25,8 @@ static inline gq_status check_params(const gq_params *p, bool uses_pack, bool us
     }
     if (uses_agg && p->agg != GQ_AGG_I32 && p->agg != GQ_AGG_I16) return GQ_ERR_INVALID_ARG;
     if (p->rng_bits != 0 && p->rng_bits != 16 && p->rng_bits != 32) return GQ_ERR_INVALID_ARG;
+    const int32_t window_bits = GQ_FLAG_WRITE_WINDOWS_OFF | GQ_FLAG_WRITE_WINDOWS_ON;
+    if ((p->flags & ~window_bits) != 0 || (p->flags & window_bits) == window_bits) return GQ_ERR_INVALID_ARG;
     return GQ_OK;
 }
 

@@ -466,7 +466,9 @@ static gq_status launch_quantize_aggregate(const GradPtrs &P, const LevelPtrs &L
     const dim3 block(kFusedBlock);
     // Write windows pay once a launch lasts many periods and a wave's K loads span about one period;
     // below these sizes the wait for the next window costs more than the cleaner read/write mix gains.
-    const bool win = !levels && K >= kWindowMinWorkers && (double)K * (double)d >= kWindowMinLoads;
+    // The caller may override the policy either way (gq_params.flags).
+    const bool by_policy = K >= kWindowMinWorkers && (double)K * (double)d >= kWindowMinLoads;
+    const bool win = !levels && !(p->flags & GQ_FLAG_WRITE_WINDOWS_OFF) && (by_policy || (p->flags & GQ_FLAG_WRITE_WINDOWS_ON));
     const uint32_t win_period = kWindowTicksPerWorker * (uint32_t)K * (uint32_t)kLaneVecs;   // a wave loads kLaneVecs KiB per worker
     const uint32_t win_open = win_period / 10u;
 #define GQ_LAUNCH(KT, LV, UH, WIN, V0, COUNT)                                                                  \

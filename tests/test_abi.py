@@ -76,11 +76,11 @@ def test_parameter_struct_layout_matches_the_header(gq):
     src = open(os.path.join(ROOT, "include", "gqsgd.h")).read()
     body = src[src.index("typedef struct {"):src.index("} gq_params;")]
     fields = re.findall(r"(int32_t|uint64_t)\s+(\w+);", body)
-    assert [n for _, n in fields] == ["scheme", "s", "pack", "agg", "rng_bits", "reserved", "seed"]
+    assert [n for _, n in fields] == ["scheme", "s", "pack", "agg", "rng_bits", "flags", "seed"]
     assert [n for n, _ in gq.gq_params._fields_] == [n for _, n in fields]
     assert C.sizeof(gq.gq_params) == 32 and gq.gq_params.seed.offset == 24 and gq.gq_params.rng_bits.offset == 16
     p = gq.make_params(1, 7, 1, 1, seed=0x1122334455667788, rng_bits=16)
-    assert (p.scheme, p.s, p.pack, p.agg, p.rng_bits, p.reserved, p.seed) == (1, 7, 1, 1, 16, 0, 0x1122334455667788)
+    assert (p.scheme, p.s, p.pack, p.agg, p.rng_bits, p.flags, p.seed) == (1, 7, 1, 1, 16, 0, 0x1122334455667788)
     assert gq.make_params(0, 5).rng_bits == 32
 
 
@@ -111,6 +111,23 @@ def test_argument_checks_need_no_device(gq):
     assert lib.gq_global_norm_static(bad_arr, 2, 16, 0, fake, None, None) == I                # misaligned gradient
     assert lib.gq_global_norm_static(arr, 2, 16, 0, None, None, None) == I                    # no output
     assert lib.gq_global_norm_static(None, 2, 16, 0, fake, None, None) == I
+    # gq_params.flags: only the two write-window bits, and not both
+    for bad_flags in (3, 4, -1, 1 << 20):
+        assert lib.gq_check_width(C.byref(P(gq.GQ_LINEAR, 127, flags=bad_flags)), 4) == I
+    for good_flags in (0, gq.GQ_FLAG_WRITE_WINDOWS_OFF, gq.GQ_FLAG_WRITE_WINDOWS_ON):
+        assert lib.gq_check_width(C.byref(P(gq.GQ_LINEAR, 127, flags=good_flags)), 4) == gq.GQ_OK
+    # gq_bucketed_quantize_aggregate
+    bk = lambda p=ok, x=arr, K=2, d=64, bucket=16, kind=0, norms=fake, agg=fake, deq=None, ws=fake, wsb=1 << 20, st=None, side=None: \
+        lib.gq_bucketed_quantize_aggregate(x, K, d, bucket, kind, C.byref(p), norms, None, agg, deq, ws, wsb, st, side)
+    assert bk(bucket=0) == I and bk(bucket=12) == I and bk(bucket=-8) == I and bk(d=-1) == I and bk(K=0) == I
+    assert bk(x=bad_arr) == I and bk(norms=None) == I and bk(agg=None) == I and bk(agg=odd) == I and bk(kind=9) == I
+    assert bk(d=1 << 40, bucket=8) == I                                                        # more than 65536 buckets
+    assert bk(st=fake, side=fake) == I                                                         # one stream given twice
+    assert bk(ws=None) == gq.GQ_ERR_WORKSPACE and bk(d=1 << 22, bucket=1 << 21, wsb=8) == gq.GQ_ERR_WORKSPACE
+    assert bk(p=P(gq.GQ_EXP, 15, 0, gq.GQ_AGG_I16), K=2) == gq.GQ_ERR_OVERFLOW
+    assert bk(d=0) == gq.GQ_OK                                                                 # nothing to do
+    assert lib.gq_bucketed_workspace_bytes(2, 64, 12) == 0 and lib.gq_bucketed_workspace_bytes(2, -1, 16) == 0
+    assert lib.gq_bucketed_workspace_bytes(4, 1 << 30, 1 << 26) == lib.gq_norm_workspace_bytes(4, 1 << 26)
     # gq_quantize
     q = lambda p, x=fake, d=16, base=0, lv=fake, sp=None: lib.gq_quantize(x, d, fake, C.byref(p), 0, base, lv, sp, None)
     assert q(ok, x=odd) == I and q(ok, lv=odd) == I and q(ok, base=2) == I and q(ok, base=-4) == I and q(ok, d=-1) == I

@@ -889,12 +889,42 @@ def test_fused_large_launches_equal_small_buckets_and_oracle(scheme, s, agg_fmt,
     for lo in range(0, d, step):
         hi = min(d, lo + step)
         gq.fused_quantize_aggregate([x[lo:hi] for x in xs], norm_t, params, lo, parts[lo:hi], parts_deq[lo:hi])
+    # and the same launch with the windows switched off by the caller
+    off = gq.make_params(scheme, s, 0, agg_fmt, seed=SI.QUANT_SEED + 1, rng_bits=rng_bits, flags=gq.GQ_FLAG_WRITE_WINDOWS_OFF)
+    plain = torch.empty(d, dtype=adt, device=DEV)
+    gq.fused_quantize_aggregate(xs, norm_t, off, 0, plain, None)
     torch.cuda.synchronize()
-    assert torch.equal(whole[:d], parts) and torch.equal(whole_deq[:d], parts_deq)
+    assert torch.equal(whole[:d], parts) and torch.equal(whole_deq[:d], parts_deq) and torch.equal(whole[:d], plain)
     assert bool((whole[d:] == 0x5A5A).all()) and bool((whole_deq[d:] == 7.0).all())
     rng = np.random.default_rng(K)
     wins = [0, d - (1 << 15)] + [int(v) for v in rng.integers(0, d - (1 << 15), 6)]
     check_windows(xs, whole[:d], nf, scheme, s, params.seed, wins, 1 << 15, rng_bits=rng_bits)
+
+
+@pytest.mark.parametrize("rng_bits", [32, 16])
+@pytest.mark.parametrize("scheme,s,agg_fmt", [(0, 127, 0), (1, 7, 1)])
+@pytest.mark.parametrize("K,d", [(1, 4099), (3, 70_001), (4, 8_191), (8, 300_003), (16, 70_000), (33, 5_001), (64, 1_000)])
+def test_write_windows_forced_on_and_off_change_no_result(scheme, s, agg_fmt, K, d, rng_bits):
+    # gq_params.flags: the time windows in which the fused kernel stores its sums change timing only.  Forced on
+    # in small launches (where the library would not use them, every worker count and the run-time-K path) and forced
+    # off, the integers and the means are those of the default policy and of the oracle.
+    xs = gaussians(K, d, seed=K + d)
+    xh = [host(x) for x in xs]
+    _, nf, _ = oracle_norm(xs, NORMS["linf"])
+    norm_t = dev_scalar(float(nf))
+    base = 8 * 4242
+    want = O.quantize_aggregate(xh, nf, scheme, s, 77, base, rng_bits=rng_bits)
+    outs = []
+    for flags in (0, gq.GQ_FLAG_WRITE_WINDOWS_ON, gq.GQ_FLAG_WRITE_WINDOWS_OFF):
+        params = gq.make_params(scheme, s, 0, agg_fmt, seed=77, rng_bits=rng_bits, flags=flags)
+        agg_out, deq_out, _, _ = run_fused(xs, norm_t, params, base, False)
+        got = host(agg_out)
+        assert np.array_equal(got[:d].astype(np.int64), want) and np.all(got[d:] == 0x5A5A)
+        outs.append((agg_out, deq_out))
+    assert all(torch.equal(o[0], outs[0][0]) and torch.equal(o[1], outs[0][1]) for o in outs[1:])
+    with pytest.raises(gq.GQError) as e:
+        run_fused(xs, norm_t, gq.make_params(scheme, s, 0, agg_fmt, seed=77, flags=3), base, False)
+    assert e.value.status == gq.GQ_ERR_INVALID_ARG
 
 
 def test_workload_c1_full_parity():

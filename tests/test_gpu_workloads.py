@@ -459,3 +459,85 @@ def test_workload_c3_in_step_averaging_at_full_size(pack):
     assert float(deq.abs().max()) <= float(nf) * (1 + 1e-6)
     diff = float(((deq.double() - exact.double()) * torch.sign(exact).double()).sum())
     assert abs(diff) <= 6.0 * unit * np.sqrt(d * 0.5)
+
+
+# ------------------------------------------------------------------------------------ per-bucket schedule
+def test_workload_c5_per_bucket_norms_two_streams_equal_the_serial_schedule():
+    # c5's shape (d = 1.5e9, K = 8, 22 buckets of 2^26 and one of 23,604,992, linear s = 15) run the way a per-bucket
+    # hook runs it: every bucket under its OWN norm.  The schedule with the next bucket's norm on a second stream
+    # must give the bits of the serial schedule, which must give the bits of the two calls made bucket by bucket;
+    # the oracle checks windows (max norm: exact, so every window; L2 norm: the buckets whose norm equals torch's
+    # binary64 reduction rounded once, since one ulp of norm can move a code)
+    cfg = SI.CONFIGS["c5"]
+    K, d, s, bucket = cfg["K"], cfg["d"], cfg["s"], cfg["bucket"]
+    xs = SI.make_workers("c5", device=DEV)
+    nb = SI.num_buckets(d, bucket)
+    p = gq.make_params(gq.GQ_LINEAR, s, gq.GQ_PACK_U4_SIGNPLANE, gq.GQ_AGG_I32, seed=SI.QUANT_SEED)
+    side = torch.cuda.Stream()
+    ws = torch.empty(gq.bucketed_workspace_bytes(K, d, bucket), dtype=torch.uint8, device=DEV)
+    for kind_name, kind in (("linf", gq.GQ_NORM_LINF), ("l2", gq.GQ_NORM_L2)):
+        # serial schedule
+        norms_s = torch.full((nb,), -1.0, device=DEV)
+        flags_s = torch.full((nb,), 77, dtype=torch.int32, device=DEV)
+        agg_s = torch.empty(d, dtype=torch.int32, device=DEV)
+        out_s = torch.empty(d, device=DEV)
+        gq.bucketed_quantize_aggregate(xs, bucket, kind, p, norms_s, flags_s, agg_s, out_s, ws)
+        torch.cuda.synchronize()
+        assert bool((flags_s == 0).all())
+        # two streams, three times over buffers refilled with garbage; the result is read by work enqueued on the
+        # main stream right behind the call, with no synchronisation in between
+        for rep in range(3):
+            norms_t = torch.full((nb,), -2.0, device=DEV)
+            flags_t = torch.full((nb,), 78, dtype=torch.int32, device=DEV)
+            agg_t = torch.full((d,), -7, dtype=torch.int32, device=DEV)
+            out_t = torch.full((d,), -7.0, device=DEV)
+            gq.bucketed_quantize_aggregate(xs, bucket, kind, p, norms_t, flags_t, agg_t, out_t, ws, side_stream=side)
+            got = (norms_t.clone(), agg_t.clone(), out_t.clone(), flags_t.clone())
+            torch.cuda.synchronize()
+            assert torch.equal(got[0], norms_s) and torch.equal(got[1], agg_s) and torch.equal(got[2], out_s)
+            assert torch.equal(got[3], flags_s)
+            del norms_t, flags_t, agg_t, out_t, got
+        # the two calls made bucket by bucket
+        n1 = torch.zeros(1, device=DEV)
+        part_a = torch.empty(bucket, dtype=torch.int32, device=DEV)
+        part_o = torch.empty(bucket, device=DEV)
+        want_norms = []
+        for b in range(nb):
+            lo, hi = b * bucket, min(d, (b + 1) * bucket)
+            xb = [x[lo:hi] for x in xs]
+            gq.global_norm(xb, kind, n1)
+            gq.fused_quantize_aggregate(xb, n1, p, lo, part_a[:hi - lo], part_o[:hi - lo])
+            torch.cuda.synchronize()
+            assert float(n1.item()) == float(norms_s[b].item())
+            assert torch.equal(part_a[:hi - lo], agg_s[lo:hi]) and torch.equal(part_o[:hi - lo], out_s[lo:hi])
+            want_norms.append(torch_norm(xb, kind_name))
+        got_norms = host(norms_s).astype(np.float64)
+        assert np.all(np.abs(got_norms - np.array(want_norms)) <= RTOL * np.array(want_norms))
+        if kind_name == "linf":
+            assert np.array_equal(host(norms_s), np.array(want_norms, dtype=np.float32))
+        # the oracle on windows, each under the norm of the bucket it lies in
+        compared = 0
+        for lo, hi in spans(d, 6, edges=[b * bucket for b in range(1, nb)]):
+            for b in range(lo // bucket, (hi - 1) // bucket + 1):
+                a, e = max(lo, b * bucket), min(hi, (b + 1) * bucket)
+                nf = np.float32(want_norms[b])
+                if np.float32(got_norms[b]) != nf:
+                    continue
+                xh = [host(x[a:e]) for x in xs]
+                A = O.quantize_aggregate(xh, nf, O.LINEAR, s, SI.QUANT_SEED, a)
+                assert np.array_equal(host(agg_s[a:e]).astype(np.int64), A), a
+                wd = O.dequantize(A, float(nf), O.LINEAR, s, K)
+                gd = host(out_s[a:e]).astype(np.float64)
+                assert np.all(np.abs(gd - wd) <= RTOL * np.abs(wd)) and np.all(gd[A == 0] == 0.0)
+                compared += 1
+        assert compared >= (80 if kind_name == "linf" else 40)
+        del agg_s, out_s
+    # the short form: d below one bucket, and a single-bucket call with a side stream (nothing to overlap)
+    small = [x[:100_003] for x in xs]
+    norms = torch.zeros(1, device=DEV)
+    o1 = torch.empty(100_003, device=DEV)
+    o2 = torch.empty(100_003, device=DEV)
+    gq.bucketed_quantize_aggregate(small, bucket, gq.GQ_NORM_LINF, p, norms, None, None, o1)
+    gq.bucketed_quantize_aggregate(small, bucket, gq.GQ_NORM_LINF, p, norms, None, None, o2, side_stream=side)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2) and float(norms.item()) == max(float(x.abs().max()) for x in small)
