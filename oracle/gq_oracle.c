@@ -60,11 +60,16 @@
  *   - Algorithm 2 (the paper's own aggregation for the exponential grid, kept beside the integer sum):
  *     values are prescaled by 1/(2 n'), n' = n rounded up to a power of two, so that a code k >= 1 of the
  *     exponential grid becomes the exponent e = s - k + 1 + log2(n') of sign * 2^-e, and e = 0 is zero
- *     (Section 4.3).  The listing takes p and m without defining them in the listing; the text has
- *     p ~ U[0,1] and P(k > b) = 2^-b.  Here k = 1 + (number of leading zero bits of a 32-bit word r), which
- *     has exactly that law for b <= 32; the paper's cap m = s+1 on k is not applied (it only matters with
- *     probability 2^-(s+1)).  One word per (tree node, coordinate): Philox counter (lo32(g/4), hi32(g/4),
- *     node, 1), word g mod 4; nodes are numbered as a binary heap (root 1, children 2h and 2h+1, worker i is
+ *     (Section 4.3).  The listing takes p and m without defining them; the text has p ~ U[0,1], m = s + 1 and
+ *     k = -floor(log2(2^-m + [p - 2^-m]_+)) = -floor(log2 p) capped at m.  p is drawn with s bits (p = r / 2^s),
+ *     the resolution at which that law is exact: P(k > b) = 2^-b for b < m, P(k = m) = 2^-(m-1).  The cap has a
+ *     consequence the paper does not mention: exponents differ by up to s - 1 between leaves but by up to
+ *     s + log2(n') - 1 between inner nodes, and a pair whose gap reaches m (same signs) or m + 1 (opposite
+ *     signs) is never rounded towards its smaller operand, which is then dropped: a relative error of at
+ *     most 2^-(s+1) of that node's sum, instead of exact unbiasedness.  Below those gaps the pair reduction
+ *     is exactly unbiased.  One field of W bits per (tree node, coordinate), W = 8, 16 or 32 for s <= 8, 16, 31,
+ *     whose top s bits are r: Philox counter (lo32(g/4), hi32(g/4), node / (32/W), 1), word g mod 4, field
+ *     node mod (32/W); nodes are numbered as a binary heap (root 1, children 2h and 2h+1, worker i is
  *     leaf n' + i, missing workers are zeros); operand 1 of a node is its child 2h.
  *     In the second-sign case the probability is printed as 2^(e2-e1-1); the text's equivalent form
  *     "k > e2 - e1 - 1" and unbiasedness both give 2^-(e2-e1-1), which is what the listing computes.
@@ -394,13 +399,19 @@ int gqo_quantize_aggregate(const float *const *x, int K, int64_t d, float norm, 
  * A pair (sign, e), sign in {-1,+1}, e >= 0, stands for 0 if e = 0 and for sign * 2^-e otherwise.
  * ========================================================================================== */
 
-/* The random integer k of Algorithm 2: P(k > b) = 2^-b.  With p = r / 2^32,
- * k > b  <=>  p < 2^-b  <=>  r has at least b leading zero bits. */
-int gqo_alg2_k(uint32_t r)
+/* The random integer k of Algorithm 2 (its first statement, derived in Section 4.3):
+ *     k = -floor(log2(2^-m + [p - 2^-m]_+)),   m = s + 1,   p uniform on [0, 1).
+ * Since 2^-m + [p - 2^-m]_+ = max(p, 2^-m), k = -floor(log2 p) capped at m: its support is 1..m,
+ * P(k > b) = P(p < 2^-b) = 2^-b for b = 0..m-1, and P(k = m) = 2^-(m-1).
+ * p is drawn with s bits, p = r / 2^s for a uniform s-bit integer r: that is the resolution at which the
+ * law above holds exactly (r = 0 is the one value with p < 2^-m, and it has probability 2^-s = 2^-(m-1)). */
+int gqo_alg2_k(uint32_t r, int s)
 {
-    int lz = 0;
-    for (uint32_t bit = 0x80000000u; bit != 0u && !(r & bit); bit >>= 1) lz++;
-    return lz + 1;
+    int m = s + 1;
+    if (r == 0u) return m;                       /* max(p, 2^-m) = 2^-m */
+    int floor_log2_r = 0;
+    while ((r >> (floor_log2_r + 1)) != 0u) floor_log2_r++;
+    return s - floor_log2_r;                     /* -floor(log2(r / 2^s)) */
 }
 
 /* Algorithm 2, the reduction of one pair (Section 4.3): x1 + x2 for x = sign * 2^-e (e = 0: zero), rounded at
@@ -445,6 +456,21 @@ uint32_t gqo_random_word_of(uint64_t seed, uint32_t word2, uint32_t word3, uint6
     return out[g % 4u];
 }
 
+/* The s random bits r of tree node `node` at coordinate g (p = r / 2^s in gqo_alg2_k).  A node's bits are the top
+ * s bits of a field of W bits, W = 8 for s <= 8, 16 for s <= 16, else 32, so that one Philox call serves the
+ * four coordinates 4c .. 4c+3 of 32 / W nodes: counter (lo32(g/4), hi32(g/4), node / (32/W), 1), word g mod 4,
+ * field number node mod (32/W) counted from the low end of the word. */
+int gqo_alg2_field_bits(int s) { return s <= 8 ? 8 : (s <= 16 ? 16 : 32); }
+
+uint32_t gqo_alg2_draw(uint64_t seed, uint32_t node, uint64_t g, int s)
+{
+    int W = gqo_alg2_field_bits(s);
+    uint32_t per_word = 32u / (uint32_t)W;
+    uint32_t word = gqo_random_word_of(seed, node / per_word, 1u, g);
+    uint32_t field = W == 32 ? word : ((word >> ((uint32_t)W * (node % per_word))) & ((1u << W) - 1u));
+    return field >> (W - s);
+}
+
 /* Tree reduction of K workers' signed exponential-grid codes with Algorithm 2.
  * out[j] = sign * e of the root (0 for zero), for the prescale 1/(2 n'), n' = 2^ceil(log2 K). */
 void gqo_exp_tree_reduce(const int32_t *const *q, int K, int64_t d, int s, uint64_t seed, uint64_t index_base,
@@ -460,8 +486,8 @@ void gqo_exp_tree_reduce(const int32_t *const *q, int K, int64_t d, int s, uint6
             ex[npad + i] = k ? s - k + 1 + L : 0;           /* 2^(k-s) / (2 n') = 2^-(s-k+1+L) */
         }
         for (int h = npad - 1; h >= 1; h--) {
-            uint32_t r = gqo_random_word_of(seed, (uint32_t)h, 1u, index_base + (uint64_t)j);
-            gqo_exp_reduce_pair(sg[2 * h], ex[2 * h], sg[2 * h + 1], ex[2 * h + 1], gqo_alg2_k(r), &sg[h], &ex[h]);
+            uint32_t r = gqo_alg2_draw(seed, (uint32_t)h, index_base + (uint64_t)j, s);
+            gqo_exp_reduce_pair(sg[2 * h], ex[2 * h], sg[2 * h + 1], ex[2 * h + 1], gqo_alg2_k(r, s), &sg[h], &ex[h]);
         }
         out[j] = ex[1] ? sg[1] * ex[1] : 0;
     }

@@ -54,7 +54,9 @@ _quantize_aggregate = _sig("gqo_quantize_aggregate", C.c_int, C.POINTER(_f32p), 
                            C.c_float, C.c_int, C.c_int, C.c_uint64, C.c_uint64, C.c_int, _i64p)
 
 
-_alg2_k = _sig("gqo_alg2_k", C.c_int, C.c_uint32)
+_alg2_k = _sig("gqo_alg2_k", C.c_int, C.c_uint32, C.c_int)
+_alg2_draw = _sig("gqo_alg2_draw", C.c_uint32, C.c_uint64, C.c_uint32, C.c_uint64, C.c_int)
+_alg2_field_bits = _sig("gqo_alg2_field_bits", C.c_int, C.c_int)
 _exp_reduce_pair = _sig("gqo_exp_reduce_pair", None, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                         C.POINTER(C.c_int), C.POINTER(C.c_int))
 _random_word_of = _sig("gqo_random_word_of", C.c_uint32, C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint64)
@@ -207,9 +209,19 @@ def quantize_aggregate(xs, norm, scheme, s, seed, index_base=0, rng_bits=32):
     return A
 
 
-def alg2_k(r):
-    """Algorithm 2: the random integer k with P(k > b) = 2^-b, from a 32-bit word."""
-    return int(_alg2_k(int(r)))
+def alg2_k(r, s):
+    """Algorithm 2, first statement: k = -floor(log2(max(p, 2^-m))), m = s + 1, for p = r / 2^s (r an s-bit integer)."""
+    return int(_alg2_k(int(r), int(s)))
+
+
+def alg2_draw(seed, node, g, s):
+    """The s random bits of tree node `node` at coordinate g (stream 1 of the Philox counter)."""
+    return int(_alg2_draw(int(seed), int(node), int(g), int(s)))
+
+
+def alg2_field_bits(s):
+    """Width W of the field a node's s random bits are the top of: 8, 16 or 32."""
+    return int(_alg2_field_bits(int(s)))
 
 
 def exp_reduce_pair(sign1, e1, sign2, e2, k):

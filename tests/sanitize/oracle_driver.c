@@ -35,7 +35,9 @@ int gqo_pack(const int32_t *q, int64_t d, int pack, uint8_t *levels, uint32_t *s
 void gqo_unpack(const uint8_t *levels, const uint32_t *signplane, int64_t d, int pack, int32_t *q);
 int gqo_quantize_aggregate(const float *const *x, int K, int64_t d, float norm, int scheme, int s, uint64_t seed,
                            uint64_t index_base, int rng_bits, int64_t *A);
-int gqo_alg2_k(uint32_t r);
+int gqo_alg2_k(uint32_t r, int s);
+uint32_t gqo_alg2_draw(uint64_t seed, uint32_t node, uint64_t g, int s);
+int gqo_alg2_field_bits(int s);
 void gqo_exp_reduce_pair(int sign1, int e1, int sign2, int e2, int k, int *sign_result, int *e_result);
 uint32_t gqo_random_word_of(uint64_t seed, uint32_t word2, uint32_t word3, uint64_t g);
 void gqo_exp_tree_reduce(const int32_t *const *q, int K, int64_t d, int s, uint64_t seed, uint64_t index_base, int32_t *out);
@@ -207,7 +209,17 @@ int main(void)
       CHECK(gqo_pack(big, 3, 2, lv, sp) == 0 && sp[0] == 2u); }
 
     /* Algorithm 2: every k, every pair of small exponents and signs, zero operands */
-    CHECK(gqo_alg2_k(0u) == 33 && gqo_alg2_k(0xFFFFFFFFu) == 1 && gqo_alg2_k(1u) == 32);
+    for (int s = 1; s <= 31; s++) {
+        uint32_t top = (s == 31 ? 0x7FFFFFFFu : ((1u << s) - 1u));
+        CHECK(gqo_alg2_k(0u, s) == s + 1 && gqo_alg2_k(top, s) == 1 && gqo_alg2_k(1u, s) == s);
+        CHECK(gqo_alg2_field_bits(s) == (s <= 8 ? 8 : s <= 16 ? 16 : 32));
+        for (uint32_t node = 1; node < 64; node += 7) {
+            uint32_t r = gqo_alg2_draw(~(uint64_t)0, node, ~(uint64_t)0 - node, s);
+            CHECK(r <= top);
+            int k = gqo_alg2_k(r, s);
+            CHECK(k >= 1 && k <= s + 1);
+        }
+    }
     for (int k = 1; k <= 33; k++)
         for (int e1 = 0; e1 <= 40; e1++)
             for (int e2 = 0; e2 <= 40; e2++)
