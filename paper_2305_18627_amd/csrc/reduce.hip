@@ -14,26 +14,49 @@ namespace gq {
 // Algorithm 2 (Section 4.3): the paper's own aggregation for the exponential grid.  Codes are moved
 // to the prescaled representation sign * 2^-e, e = s - k + 1 + log2(n'), and reduced pairwise in
 // tree order; every node rounds its sum to a neighbouring power of two with the random integer
-// k, P(k > b) = 2^-b.  A lane owns four coordinates and walks the tree depth first with a stack of
-// log2(n') + 1 partial results, so the K code words are consumed as they arrive.
+// k = -floor(log2(max(p, 2^-m))), m = s + 1, p = r / 2^s for the node's s random bits r.  A lane owns four
+// coordinates and walks the tree depth first with a stack of log2(n') + 1 partial results, so the K code
+// words are consumed as they arrive.  A node's bits are the top s bits of a field of W = 8, 16 or 32 bits
+// (s <= 8, 16, 31) of the Philox call of its group of 32 / W nodes, so one call serves 4, 2 or 1 nodes.
+//
+// Two arithmetic paths give the same results.  For s <= 16 a partial result is held as the binary32 number
+// sign * 2^j it stands for (scaled by 2^(s + log2(n') + 1), so j = s + log2(n') + 1 - e >= 1, zero is 0.0f):
+// the sum of two of them is exact in binary32 (exponents at most 21 apart), and the random rounding to a
+// neighbouring power of two is an integer add on its mantissa followed by a mask, as in the exponential
+// quantiser.  For s > 16 (32-bit fields) the integer form of the listing is kept.
 // =============================================================================================
 constexpr int kReduceBlock = 128;
 
-// A partial result inside the kernel: sg carries the sign in its top bit (its other bits are free), e is
-// the exponent of 2^-e, and ZERO is stood for by any e >= kZeroE / 2.  With zero as a huge exponent the
-// listing's special cases for zero operands disappear: 2^-e + "2^-huge" never rounds away from 2^-e,
-// because the random integer k is at most 33.
+// ---- binary32 path ----------------------------------------------------------------------------------------
+// x1, x2: sign * 2^j or 0.  A = (2^s - 1 - r) << (23 - s) for the node's s random bits r.
+//   same signs      mantissa of the sum is 2^(23-gap); adding A carries into the exponent iff r < 2^(s-gap),
+//                   i.e. iff k > gap: up to the next power of two, never for gap > s (the cap k <= m)
+//   opposite signs  the sum 2^ja - 2^jb has exponent ja - 1 and mantissa 2^23 - 2^(24-gap); adding
+//                   B = A ^ 0x7FFFFF = (r << (23-s)) | (2^(23-s) - 1) carries iff r >= 2^(s+1-gap), i.e. iff NOT k > gap - 1:
+//                   the result stays at 2^ja, else goes down to 2^(ja-1); always stays for gap > s + 1 (the cap)
+//   a zero operand  leaves a zero mantissa: no carry, the other operand passes unchanged; x - x = +0
+__device__ __forceinline__ float alg2_pair_f32(float x1, float x2, uint32_t A)
+{
+    const float sum = x1 + x2;
+    const uint32_t opposite = (uint32_t)((int)(__float_as_uint(x1) ^ __float_as_uint(x2)) >> 31);   // all ones iff the signs differ
+    const uint32_t R = A ^ (opposite & 0x7FFFFFu);
+    return __uint_as_float((__float_as_uint(sum) + R) & 0xFF800000u);
+}
+
+// ---- integer path (32-bit fields) -------------------------------------------------------------------------
+// A partial result: sg carries the sign in its top bit (its other bits are free), e is the exponent of 2^-e,
+// and ZERO is stood for by any e >= kZeroE / 2.  With zero as a huge exponent the listing's special cases for
+// zero operands disappear: 2^-e + "2^-huge" never rounds away from 2^-e, because k is at most m <= 32.
 constexpr int kZeroE = 1 << 20;
 struct Pow2 { int sg; int e; };
 
-// One node of Algorithm 2: the sum of two signed powers of two, rounded to a neighbouring power of two.
-// a = the operand with the smaller exponent (operand 1 on a tie), diff = e_b - e_a.
+// One node: a = the operand with the smaller exponent (operand 1 on a tie), diff = e_b - e_a.
 //   same signs      2^-ea + 2^-eb lies in [2^-ea, 2^-(ea-1)]: up to 2^-(ea-1) iff k > diff
 //   opposite signs  2^-ea - 2^-eb lies in [2^-(ea+1), 2^-ea]: down to 2^-(ea+1) iff k > diff - 1; 0 if diff = 0
-// with k = 1 + (leading zeros of r), so k > t iff clz(r) >= t.
-__device__ __forceinline__ Pow2 alg2_pair(const Pow2 &x1, const Pow2 &x2, uint32_t r)
+// with k = 1 + min(leading zeros of the 32-bit field, s), so k > t iff that minimum is >= t.
+__device__ __forceinline__ Pow2 alg2_pair_int(const Pow2 &x1, const Pow2 &x2, uint32_t r, int s)
 {
-    const int lead = __clz((int)r);                                  // leading zeros of r, 32 for r = 0
+    const int lead = min(__clz((int)r), s);                          // k - 1; the cap m = s + 1 on k
     const bool first = x1.e <= x2.e;
     const int ea = min(x1.e, x2.e), eb = max(x1.e, x2.e);
     const int opp = (int)((uint32_t)(x1.sg ^ x2.sg) >> 31);          // 1 iff the signs differ
@@ -45,12 +68,34 @@ __device__ __forceinline__ Pow2 alg2_pair(const Pow2 &x1, const Pow2 &x2, uint32
     return o;
 }
 
-template <int NPAD, bool UNIFORM_HI>
+// Was `node` the first of its group of PER nodes to be visited by the depth-first walk?  Nodes of one tree
+// level are visited in increasing order and a group lies inside one level, except the group of nodes 1..PER-1,
+// whose first visited member is node 2 (node 1 in a tree of two leaves).
+template <int NPAD, int PER> __device__ __forceinline__ constexpr bool first_of_group(int node)
+{
+    if (node % PER == 0) return true;
+    if (node >= PER) return false;
+    return NPAD == 2 ? node == 1 : (PER == 2 ? node == 1 : node == 2);
+}
+
+template <int NPAD, bool UNIFORM_HI, int W>
 __global__ void __launch_bounds__(kReduceBlock)
 exp_reduce_kernel(LevelCPtrs Lv, int K, int64_t d, int s, uint64_t seed, uint64_t call_base,
                   const float *__restrict__ norm, void *__restrict__ reduced_out, float *__restrict__ deq_out)
 {
     constexpr int L = NPAD == 1 ? 0 : NPAD == 2 ? 1 : NPAD == 4 ? 2 : NPAD == 8 ? 3 : NPAD == 16 ? 4 : NPAD == 32 ? 5 : 6;
+    constexpr bool kFloat = W < 32;
+    constexpr int PER = 32 / W;                              // tree nodes served by one Philox call
+    // binary32 path: the value sign * 2^min(|q|, s) of every code byte q (0 for q = 0)
+    __shared__ float leaf_value[kFloat ? 256 : 1];
+    if (kFloat) {
+        for (int b = threadIdx.x; b < 256; b += kReduceBlock) {
+            const int q = (int)(int8_t)b;
+            const float v = q ? __uint_as_float((uint32_t)(127 + min(abs(q), s)) << 23) : 0.0f;
+            leaf_value[b] = q < 0 ? -v : v;
+        }
+        __syncthreads();
+    }
     const int64_t v = (int64_t)blockIdx.x * kReduceBlock + threadIdx.x;
     const int64_t nfull = d >> 2;
     const int nvalid = v < nfull ? 4 : (v == nfull ? (int)(d & 3) : 0);
@@ -73,15 +118,11 @@ exp_reduce_kernel(LevelCPtrs Lv, int K, int64_t d, int s, uint64_t seed, uint64_
         for (int i = 0; i < nvalid; i++) t |= (uint32_t)b[i] << (8 * i);
         return t;
     };
-    // code k >= 1 of the exponential grid -> e = s - k + 1 + L; code 0 is zero
-    auto leaf = [&](uint32_t word, int i) -> Pow2 {
-        const int q = (int)(int8_t)(word >> (8 * i));
-        Pow2 x;
-        x.sg = q;
-        x.e = q ? s + 1 + L - abs(q) : kZeroE;
-        return x;
-    };
-    int st_sg[L + 1][4], st_e[L + 1][4];                    // the stack of partial results (sign carrier, exponent)
+    // the stack of partial results: binary32 values, or (sign carrier, exponent) pairs
+    float st_f[kFloat ? L + 1 : 1][4];
+    int st_sg[kFloat ? 1 : L + 1][4], st_e[kFloat ? 1 : L + 1][4];
+    // the Philox words of the node groups in use, one slot per tree level; the binary32 path keeps them complemented
+    uint32_t grp[L + 1][4];
     constexpr int kBatch = NPAD < 8 ? NPAD : 8;
 #pragma unroll
     for (int w0 = 0; w0 < NPAD; w0 += kBatch) {
@@ -93,16 +134,39 @@ exp_reduce_kernel(LevelCPtrs Lv, int K, int64_t d, int s, uint64_t seed, uint64_
             const int i = w0 + j;                            // leaf index; the stack depth is popcount(i)
             int top = __builtin_popcount((unsigned)i);
 #pragma unroll
-            for (int c = 0; c < 4; c++) { const Pow2 x = leaf(words[j], c); st_sg[top][c] = x.sg; st_e[top][c] = x.e; }
+            for (int c = 0; c < 4; c++) {
+                if (kFloat) {
+                    st_f[top][c] = leaf_value[(words[j] >> (8 * c)) & 255u];
+                } else {
+                    // code k >= 1 of the exponential grid -> e = s - k + 1 + L; code 0 is zero
+                    const int q = (int)(int8_t)(words[j] >> (8 * c));
+                    st_sg[top][c] = q;
+                    st_e[top][c] = q ? s + 1 + L - abs(q) : kZeroE;
+                }
+            }
 #pragma unroll
             for (int lvl = 1; lvl <= L; lvl++) {
                 if (((i + 1) & ((1 << lvl) - 1)) == 0) {     // a subtree of 2^lvl leaves is complete
-                    const uint32_t node = (uint32_t)((NPAD >> lvl) + (i >> lvl));   // heap numbering
-                    const Words4 r = philox4x32_10(c_lo, c_hi, node, 1u, k0, k1);
+                    const int node = (NPAD >> lvl) + (i >> lvl);            // heap numbering
+                    // the root shares its group with nodes 2 and 3 (one level down) when a call serves four nodes
+                    const int slot = (PER == 4 && node == 1 && NPAD >= 4) ? lvl - 1 : lvl;
+                    if (first_of_group<NPAD, PER>(node)) {
+                        const Words4 r = philox4x32_10(c_lo, c_hi, (uint32_t)(node / PER), 1u, k0, k1);
+#pragma unroll
+                        for (int c = 0; c < 4; c++) grp[slot][c] = kFloat ? ~r.w[c] : r.w[c];
+                    }
 #pragma unroll
                     for (int c = 0; c < 4; c++) {
-                        const Pow2 o = alg2_pair(Pow2{st_sg[top - 1][c], st_e[top - 1][c]}, Pow2{st_sg[top][c], st_e[top][c]}, r.w[c]);
-                        st_sg[top - 1][c] = o.sg; st_e[top - 1][c] = o.e;
+                        if (kFloat) {
+                            // the top s bits of the node's complemented field, moved to the top of the mantissa
+                            const uint32_t A = __builtin_amdgcn_ubfe(grp[slot][c], (uint32_t)(W * (node % PER) + W - s), (uint32_t)s)
+                                               << (23 - s);
+                            st_f[top - 1][c] = alg2_pair_f32(st_f[top - 1][c], st_f[top][c], A);
+                        } else {
+                            const Pow2 o = alg2_pair_int(Pow2{st_sg[top - 1][c], st_e[top - 1][c]}, Pow2{st_sg[top][c], st_e[top][c]},
+                                                         grp[slot][c], s);
+                            st_sg[top - 1][c] = o.sg; st_e[top - 1][c] = o.e;
+                        }
                     }
                     top--;
                 }
@@ -112,8 +176,15 @@ exp_reduce_kernel(LevelCPtrs Lv, int K, int64_t d, int s, uint64_t seed, uint64_
     int root[4];                                            // sign * e of the root, 0 for zero
 #pragma unroll
     for (int c = 0; c < 4; c++) {
-        const int e = st_e[0][c] >= kZeroE / 2 ? 0 : st_e[0][c];
-        root[c] = st_sg[0][c] < 0 ? -e : e;
+        if (kFloat) {
+            const uint32_t b = __float_as_uint(st_f[0][c]);
+            const int j = (int)((b >> 23) & 255u) - 127;    // the root stands for 2^j, j = s + L + 1 - e
+            const int e = (b & 0x7F800000u) ? s + L + 1 - j : 0;
+            root[c] = (b >> 31) ? -e : e;
+        } else {
+            const int e = st_e[0][c] >= kZeroE / 2 ? 0 : st_e[0][c];
+            root[c] = st_sg[0][c] < 0 ? -e : e;
+        }
     }
     if (reduced_out) {
         const uint32_t wout = (uint32_t)(root[0] & 255) | ((uint32_t)(root[1] & 255) << 8) |
@@ -289,13 +360,12 @@ gq_status gq_exp_reduce(const void *const *levels, int K, int64_t d, const gq_pa
     hipStream_t s = (hipStream_t)hip_stream;
     int npad = 1;
     while (npad < K) npad <<= 1;
-#define GQ_RED(N)                                                                                              \
-    do {                                                                                                       \
-        if (one_stretch) hipLaunchKernelGGL((exp_reduce_kernel<N, true>), grid, block, 0, s, Lv, K, d, p->s, p->seed, \
-                                            call_base, norm, reduced_out, dequant_out);                        \
-        else hipLaunchKernelGGL((exp_reduce_kernel<N, false>), grid, block, 0, s, Lv, K, d, p->s, p->seed,       \
-                                call_base, norm, reduced_out, dequant_out);                                    \
-    } while (0)
+    // width of the field a node's s random bits are the top of
+    const int field_bits = p->s <= 8 ? 8 : (p->s <= 16 ? 16 : 32);
+#define GQ_RED3(N, UH, FB) hipLaunchKernelGGL((exp_reduce_kernel<N, UH, FB>), grid, block, 0, s, Lv, K, d, p->s, p->seed, \
+                                              call_base, norm, reduced_out, dequant_out)
+#define GQ_RED2(N, UH) do { if (field_bits == 8) GQ_RED3(N, UH, 8); else if (field_bits == 16) GQ_RED3(N, UH, 16); else GQ_RED3(N, UH, 32); } while (0)
+#define GQ_RED(N) do { if (one_stretch) GQ_RED2(N, true); else GQ_RED2(N, false); } while (0)
     switch (npad) {
     case 1: GQ_RED(1); break;
     case 2: GQ_RED(2); break;
@@ -306,6 +376,8 @@ gq_status gq_exp_reduce(const void *const *levels, int K, int64_t d, const gq_pa
     default: GQ_RED(64); break;
     }
 #undef GQ_RED
+#undef GQ_RED2
+#undef GQ_RED3
     return launched();
 }
 
