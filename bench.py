@@ -166,7 +166,7 @@ def time_rows(gq, torch, xs, norm, params, cfg, args):
     if pack == gq.GQ_PACK_I8 and d < (1 << 32):
         # Algorithm 1's sparse branch: compaction of every worker's non-zero codes, then the sum of the K lists
         cnts = [torch.zeros(1, dtype=torch.int64, device=dev) for _ in range(K)]
-        ws = torch.empty(max(gq.compact_workspace_bytes(d), 4), dtype=torch.uint8, device=dev)
+        ws = torch.empty(gq.compact_workspace_bytes(d), dtype=torch.uint8, device=dev)
         probe_i = torch.empty(1, dtype=torch.int32, device=dev)
         probe_v = torch.empty(1, dtype=torch.int8, device=dev)
         for i in range(K):
@@ -181,7 +181,8 @@ def time_rows(gq, torch, xs, norm, params, cfg, args):
                 gq.compact(lvs[i], d, p, idxs[i], vals[i], cnts[i], ws)
 
         tot = float(sum(nnz))
-        rows["compact_xK"] = timed(compact_all, 2.0 * K * d + 5.0 * tot)
+        # the method's bytes: every code read once, every pair (4-byte index + 1-byte code) written once
+        rows["compact_xK"] = timed(compact_all, 1.0 * K * d + 5.0 * tot)
         if aggf == gq.GQ_AGG_I32:
             rows["sparse_aggregate"] = timed(lambda: gq.sparse_aggregate(idxs, vals, cnts, d, p, agg), 4.0 * d + 5.0 * tot)
         rows["nonzero_fraction"] = tot / (float(K) * d)

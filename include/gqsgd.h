@@ -254,8 +254,11 @@ gq_status gq_avg_reduce(const void *const *levels /* host */, int K, int64_t d, 
  *   indices_out      device uint32[capacity]; values_out device int8[capacity]
  *   count_out        device uint64[1]: the TRUE number of non-zero codes; if it exceeds `capacity` only the
  *                    first `capacity` pairs were written and the caller must retry with larger buffers
- *   workspace        device scratch of at least gq_compact_workspace_bytes(d) bytes (block counts), overwritten
- * The result is unique (sorted by index) and does not depend on scheduling. */
+ *   workspace        device scratch of at least gq_compact_workspace_bytes(d) bytes, 8-byte aligned, overwritten (the
+ *                    words of a scan over spans of 32768 codes); not to be shared by calls that may overlap
+ * The codes are read once and only the list is written.  The result is unique (sorted by index) and does not
+ * depend on scheduling.  count_out = 2^64 - 1 reports that the scan over the blocks gave up waiting (it cannot
+ * in a working launch: every block waits only for blocks that started before it); the lists are then incomplete. */
 size_t gq_compact_workspace_bytes(int64_t d);
 gq_status gq_compact(const void *levels, int64_t d, const gq_params *p /* host */, uint32_t *indices_out,
                      int8_t *values_out, int64_t capacity, uint64_t *count_out,

@@ -271,7 +271,7 @@ def compact(levels, d, params, indices_out, values_out, count_out, workspace=Non
     _need(levels, int(d), "levels"); _need(count_out, 8, "count_out")
     _need(values_out, indices_out.numel(), "values_out"); _need(indices_out, 0, "indices_out")
     if workspace is None:
-        workspace = torch.empty(max(compact_workspace_bytes(d), 4), dtype=torch.uint8, device=count_out.device)
+        workspace = torch.empty(compact_workspace_bytes(d), dtype=torch.uint8, device=count_out.device)
     st = _lib.gq_compact(_ptr(levels), int(d), C.byref(params), _ptr(indices_out), _ptr(values_out),
                          indices_out.numel(), _ptr(count_out), _ptr(workspace),
                          workspace.numel() * workspace.element_size(), _stream(stream))

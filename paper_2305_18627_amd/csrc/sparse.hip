@@ -11,16 +11,15 @@
 namespace gq {
 
 // =============================================================================================
-// Algorithm 1's sparse branch, the sparse branch.  Sender side: the (index, code) pairs of a worker's
-// non-zero int8 codes in increasing index order, by a count pass, a one-block scan of the block
-// counts and a write pass that ranks the non-zeros inside a block with wave scans.  Receiver side:
-// the K sorted lists are merged tile by tile into the dense int32 sum.
+// Algorithm 1's sparse branch.  Sender side: the (index, code) pairs of a worker's non-zero int8 codes in
+// increasing index order, in one pass over the codes (a chained scan over the blocks gives every block its
+// place in the list; the non-zeros inside a block are ranked with wave scans).  Receiver side: the K sorted
+// lists are merged tile by tile into the dense int32 sum.
 // =============================================================================================
 constexpr int kCompactBlock = 256;
 constexpr int kCompactTile = kCompactBlock * 16;        // codes per tile: one 128-bit load per thread
-constexpr int kCompactTiles = 4;                        // consecutive tiles per block: fewer, larger block counts to scan
+constexpr int kCompactTiles = 8;                        // consecutive tiles per span: 32 KiB of codes
 constexpr int kCompactSpan = kCompactTile * kCompactTiles;
-constexpr int kScanBlock = 1024;
 
 __device__ __forceinline__ uint32_t nonzero_bytes(uint32_t x)    // 0x80 in every byte of x that is not zero
 {
@@ -67,80 +66,216 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *s
     return base + incl - v;
 }
 
-__global__ void __launch_bounds__(kCompactBlock)
-compact_count_kernel(const uint8_t *__restrict__ lv, int64_t d, uint32_t *__restrict__ block_counts)
+// ---------------------------------------------------------------------------------------------------------
+// Sender side in ONE pass over the codes: a block counts the non-zeros of its span, learns how many lie before
+// the span from the counts the blocks before it have published, and writes its pairs.  The codes are read once
+// and nothing but the list is written: d + 5 * nnz bytes, the method's own traffic.
+//
+// Spans of kCompactSpan codes are grouped by 64.  One word per span and one word per group (plain stores and loads, no
+// read-modify-write atomics: those serialise chip-wide on one address, measured at about 20 ns each):
+//   span word    bits 31..0 the count of the span, bit 32 set once it is published
+//   group word   bits 39..0 the sum of the counts of the group's 64 spans, bit 40 set once it is published
+// A block publishes its count as soon as it has counted, before it waits for anybody.  What lies before block b
+// is the sum of all earlier groups plus the counts of the earlier blocks of its own group; the last block of a
+// group, which has just added up its 63 predecessors for itself, publishes the group's word.  No block waits for
+// another block's prefix, so the waits do not chain: a few hundred words are read once or twice per block.
+//
+// Why every wait ends.  One workgroup per span.  Workgroups of a one-dimensional grid are handed to the eight XCDs
+// in turn and each XCD starts its share in increasing order.  Let m be the smallest span not yet finished: every
+// workgroup of m's XCD before m has finished, so m has a free slot and has started; it publishes its count after a
+// bounded amount of work of its own (loads, a count, a block scan) and waits for nothing before that.  A span waits
+// only for counts of earlier spans and for sums of earlier groups, whose writers wait only for counts of their own
+// group: every word m waits for is there, m finishes, and the argument repeats.  The wait is bounded all the same
+// (kPrefixMaxPolls polls of about a microsecond): a workgroup that gives up writes nothing and raises count_out to
+// 2^64 - 1, which no real count reaches.
+// ---------------------------------------------------------------------------------------------------------
+constexpr int kGroupBlocks = 64;
+constexpr uint64_t kPublished = 1ull << 32;
+constexpr uint64_t kGroupPublished = 1ull << 40;
+constexpr int kPrefixMaxPolls = 1 << 21;
+
+__global__ void __launch_bounds__(kBlock) compact_clear_kernel(uint64_t *__restrict__ state, int64_t words, uint64_t *__restrict__ count_out)
 {
-    __shared__ uint32_t sh[kCompactBlock / 64];
-    const int64_t t0 = (int64_t)blockIdx.x * (kCompactBlock * kCompactTiles) + threadIdx.x;
-    u32x4 c[kCompactTiles];
-#pragma unroll
-    for (int j = 0; j < kCompactTiles; j++) c[j] = load_code_unit(lv, t0 + (int64_t)j * kCompactBlock, d);
-    uint32_t mine = 0;
-#pragma unroll
-    for (int j = 0; j < kCompactTiles; j++) mine += count_unit(c[j]);
-    uint32_t total;
-    block_exclusive_scan<kCompactBlock>(mine, sh, &total);
-    if (threadIdx.x == 0) block_counts[blockIdx.x] = total;
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i < words) state[i] = 0;
+    if (i == 0) *count_out = 0;
 }
 
-// One block: counts[0..n) -> exclusive offsets in place; the grand total goes to *total_out.
-// The counts are taken kScanBlock at a time with consecutive lanes on consecutive words; the running
-// total is carried from one round to the next.
-__global__ void __launch_bounds__(kScanBlock)
-compact_scan_kernel(uint32_t *__restrict__ counts, int64_t n, uint64_t *__restrict__ total_out)
+__device__ __forceinline__ uint64_t state_load(const uint64_t *p)
 {
-    __shared__ uint32_t sh[kScanBlock / 64];
-    uint32_t carry = 0;
-    for (int64_t base = 0; base < n; base += kScanBlock) {
-        const int64_t i = base + threadIdx.x;
-        const uint32_t c = i < n ? counts[i] : 0u;
-        uint32_t total;
-        const uint32_t excl = block_exclusive_scan<kScanBlock>(c, sh, &total);
-        if (i < n) counts[i] = carry + excl;
-        carry += total;
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ uint64_t wave_sum_u64(uint64_t v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const uint32_t lo = (uint32_t)__shfl_xor((int)(uint32_t)v, off, 64), hi = (uint32_t)__shfl_xor((int)(uint32_t)(v >> 32), off, 64);
+        v += ((uint64_t)hi << 32) | lo;
     }
-    if (threadIdx.x == 0) *total_out = (uint64_t)carry;
+    return v;
 }
 
-// A block takes its kCompactTiles tiles one after the other.  The pairs of a tile are first ranked into LDS (a
-// tile never holds more than kCompactTile of them) and then copied out with consecutive lanes writing
-// consecutive list entries; the list position runs on from tile to tile.
-__global__ void __launch_bounds__(kCompactBlock)
-compact_write_kernel(const uint8_t *__restrict__ lv, int64_t d, const uint32_t *__restrict__ block_offsets,
-                     uint32_t *__restrict__ indices_out, int8_t *__restrict__ values_out, int64_t capacity)
+// Number of non-zero codes before span `span`: the counts of the earlier spans of its own group plus the sums of
+// the earlier groups.  Run by one whole wave; the result is uniform.  Both kinds of word are asked for in the same
+// round trip (a poll queues behind the bulk reads of the whole chip, so trips are what costs).  *in_group receives the
+// own group's part as soon as it is complete and *in_group_ready is set (the caller then publishes the group's sum
+// if it is the group's last span, and calls again for the rest).  Returns true once everything is there, false
+// after an unsuccessful poll; the caller counts those.
+struct Before { uint64_t in_group, groups; bool in_group_ready, groups_ready; int64_t next_group; };
+
+__device__ __forceinline__ void poll_before(const uint64_t *span_words, const uint64_t *group_words, int64_t span, Before *st)
 {
-    __shared__ uint32_t sh[kCompactBlock / 64];
+    const int lane = (int)(threadIdx.x & 63u);
+    const int64_t group = span / kGroupBlocks;
+    const int member = (int)(span - group * kGroupBlocks);
+    uint64_t w_in = kPublished, w_gr = kGroupPublished;
+    if (!st->in_group_ready && lane < member) w_in = state_load(span_words + group * kGroupBlocks + lane);
+    if (!st->groups_ready && st->next_group + lane < group) w_gr = state_load(group_words + st->next_group + lane);
+    if (!st->in_group_ready && __ballot((w_in & kPublished) == 0) == 0ull) {
+        st->in_group = wave_sum_u64(w_in & 0xFFFFFFFFull);
+        st->in_group_ready = true;
+    }
+    if (!st->groups_ready && __ballot((w_gr & kGroupPublished) == 0) == 0ull) {
+        st->groups += wave_sum_u64(w_gr & (kGroupPublished - 1ull));
+        st->next_group += 64;
+        if (st->next_group >= group) st->groups_ready = true;
+    }
+}
+
+// Exclusive prefix sums over the block of kCompactTiles counts per thread at once.  Two counts share a 32-bit
+// word (a thread counts at most 16 non-zeros per tile and a tile holds at most 4096, so 16 bits each never
+// carry into each other), which halves the shuffles, and all tiles share the two barriers.
+// rank[j] receives the number of non-zeros of tile j held by the threads before this one, total[j] the tile's count.
+// sh must hold (kCompactBlock / 64) * (kCompactTiles / 2) words.  Every thread must call it.
+__device__ __forceinline__ void block_scan_tiles(const uint32_t *cnt, uint32_t *sh, uint32_t *rank, uint32_t *total)
+{
+    constexpr int kPairs = kCompactTiles / 2, kWaves = kCompactBlock / 64;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t incl[kPairs];
+#pragma unroll
+    for (int q = 0; q < kPairs; q++) incl[q] = cnt[2 * q] | (cnt[2 * q + 1] << 16);
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+#pragma unroll
+        for (int q = 0; q < kPairs; q++) {
+            const uint32_t t = (uint32_t)__shfl_up((int)incl[q], off, 64);
+            if (lane >= off) incl[q] += t;
+        }
+    }
+    if (lane == 63) {
+#pragma unroll
+        for (int q = 0; q < kPairs; q++) sh[wave * kPairs + q] = incl[q];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < kPairs; q++) {
+        uint32_t before = 0, sum = 0;
+#pragma unroll
+        for (int i = 0; i < kWaves; i++) {
+            const uint32_t w = sh[i * kPairs + q];
+            if (i < wave) before += w;
+            sum += w;
+        }
+        const uint32_t excl = before + incl[q] - (cnt[2 * q] | (cnt[2 * q + 1] << 16));
+        rank[2 * q] = excl & 0xFFFFu;       rank[2 * q + 1] = excl >> 16;
+        total[2 * q] = sum & 0xFFFFu;       total[2 * q + 1] = sum >> 16;
+    }
+    __syncthreads();
+}
+
+__global__ void __launch_bounds__(kCompactBlock)
+compact_onepass_kernel(const uint8_t *__restrict__ lv, int64_t d, uint64_t *__restrict__ state, int64_t nspans,
+                       uint32_t *__restrict__ indices_out, int8_t *__restrict__ values_out, int64_t capacity,
+                       uint64_t *__restrict__ count_out)
+{
+    __shared__ uint32_t sh[(kCompactBlock / 64) * (kCompactTiles / 2)];
     __shared__ uint32_t s_idx[kCompactTile];
     __shared__ int8_t s_val[kCompactTile];
-    const int64_t t0 = (int64_t)blockIdx.x * (kCompactBlock * kCompactTiles) + threadIdx.x;
+    __shared__ int64_t s_base;
+    uint64_t *span_words = state + 2;
+    uint64_t *group_words = span_words + nspans;
+    const int64_t span = blockIdx.x;
+    const int64_t t0 = span * (kCompactBlock * kCompactTiles) + threadIdx.x;
     u32x4 c[kCompactTiles];
 #pragma unroll
     for (int j = 0; j < kCompactTiles; j++) c[j] = load_code_unit(lv, t0 + (int64_t)j * kCompactBlock, d);
-    int64_t base = (int64_t)block_offsets[blockIdx.x];
+    uint32_t cnt[kCompactTiles], rank[kCompactTiles], total[kCompactTiles];
+#pragma unroll
+    for (int j = 0; j < kCompactTiles; j++) cnt[j] = count_unit(c[j]);
+    block_scan_tiles(cnt, sh, rank, total);
+    uint32_t span_total = 0;
+#pragma unroll
+    for (int j = 0; j < kCompactTiles; j++) span_total += total[j];
+    // the span's count is what the other workgroups wait for: out with it before anything else
+    if (threadIdx.x == 0) __hip_atomic_store(span_words + span, kPublished | span_total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
+    // The pairs of a tile are ranked into LDS (a tile never holds more than kCompactTile of them) and then copied
+    // out with consecutive lanes writing consecutive list entries; the list position runs on from tile to tile.
+    // The first tile is ranked while the published count travels; only then does wave 0 ask what lies before.
+    int64_t base = 0;
 #pragma unroll
     for (int j = 0; j < kCompactTiles; j++) {
+        if (j > 0 && total[j] == 0) continue;                // uniform over the block: nothing to rank or to copy
         const int64_t t = t0 + (int64_t)j * kCompactBlock;
-        uint32_t total;
-        uint32_t rank = block_exclusive_scan<kCompactBlock>(count_unit(c[j]), sh, &total);
-        const uint32_t w[4] = {c[j].x, c[j].y, c[j].z, c[j].w};
+        if (cnt[j] != 0) {
+            uint32_t r = rank[j];
+            const uint32_t w[4] = {c[j].x, c[j].y, c[j].z, c[j].w};
 #pragma unroll
-        for (int i = 0; i < 16; i++) {
-            const uint32_t b = (w[i >> 2] >> (8 * (i & 3))) & 255u;
-            if (b != 0u) {
-                s_idx[rank] = (uint32_t)((t << 4) + i);
-                s_val[rank] = (int8_t)b;
-                rank++;
+            for (int i = 0; i < 16; i++) {
+                const uint32_t b = (w[i >> 2] >> (8 * (i & 3))) & 255u;
+                if (b != 0u) {
+                    s_idx[r] = (uint32_t)((t << 4) + i);
+                    s_val[r] = (int8_t)b;
+                    r++;
+                }
             }
         }
-        __syncthreads();
-        for (uint32_t e = threadIdx.x; e < total; e += kCompactBlock) {
+        if (j == 0) {
+            if (threadIdx.x < 64) {                          // wave 0
+                Before st = {0, 0, false, span / kGroupBlocks == 0, 0};
+                bool group_sum_out = span % kGroupBlocks != kGroupBlocks - 1;     // only a group's last span owes one
+                int polls = 0;
+                bool gave_up = false;
+                for (;;) {
+                    poll_before(span_words, group_words, span, &st);
+                    // the group's last span publishes the group's sum as soon as it has it, before it waits on
+                    if (st.in_group_ready && !group_sum_out) {
+                        if (threadIdx.x == 0)
+                            __hip_atomic_store(group_words + span / kGroupBlocks, kGroupPublished | (st.in_group + span_total),
+                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        group_sum_out = true;
+                    }
+                    if (st.in_group_ready && st.groups_ready) break;
+                    if (++polls > kPrefixMaxPolls) { gave_up = true; break; }
+                    __builtin_amdgcn_s_sleep(4);
+                }
+                if (threadIdx.x == 0) {
+                    const uint64_t before = st.in_group + st.groups;
+                    if (gave_up) {
+                        atomicMax(reinterpret_cast<unsigned long long *>(count_out), ~0ull);
+                        s_base = -1;
+                    } else {
+                        if (span == nspans - 1)
+                            atomicMax(reinterpret_cast<unsigned long long *>(count_out), (unsigned long long)(before + span_total));
+                        s_base = (int64_t)before;
+                    }
+                }
+            }
+            __syncthreads();
+            base = s_base;
+            if (base < 0) return;                            // uniform over the block
+        } else {
+            __syncthreads();
+        }
+        for (uint32_t e = threadIdx.x; e < total[j]; e += kCompactBlock) {
             if (base + e < capacity) {
                 indices_out[base + e] = s_idx[e];
                 values_out[base + e] = s_val[e];
             }
         }
-        base += total;
-        __syncthreads();                                 // the staging area is reused by the next tile
+        base += total[j];
+        __syncthreads();                                     // the staging area is reused by the next tile
     }
 }
 
@@ -236,7 +371,8 @@ size_t gq_compact_workspace_bytes(int64_t d)
 {
     if (d < 0 || d > 0xFFFFFFFFLL) return 0;
     const int64_t blocks = (d + kCompactSpan - 1) / kCompactSpan;
-    return (size_t)(blocks > 0 ? blocks : 1) * sizeof(uint32_t);
+    const int64_t groups = (blocks + kGroupBlocks - 1) / kGroupBlocks;
+    return (size_t)(2 + blocks + groups) * sizeof(uint64_t); // two spare words, a word per block and per group of 64
 }
 
 gq_status gq_compact(const void *levels, int64_t d, const gq_params *p, uint32_t *indices_out, int8_t *values_out,
@@ -250,21 +386,19 @@ gq_status gq_compact(const void *levels, int64_t d, const gq_params *p, uint32_t
     if (d > 0 && !aligned(levels, 16)) return GQ_ERR_INVALID_ARG;
     if (capacity > 0 && (!aligned(indices_out, 4) || !values_out)) return GQ_ERR_INVALID_ARG;
     if (!workspace || workspace_bytes < gq_compact_workspace_bytes(d)) return GQ_ERR_WORKSPACE;
-    if (!aligned(workspace, 4)) return GQ_ERR_INVALID_ARG;
+    if (!aligned(workspace, 8)) return GQ_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)hip_stream;
-    uint32_t *counts = reinterpret_cast<uint32_t *>(workspace);
+    uint64_t *state = reinterpret_cast<uint64_t *>(workspace);
     const int64_t blocks = (d + kCompactSpan - 1) / kCompactSpan;
     if (!grid_fits(blocks, kCompactBlock)) return GQ_ERR_INVALID_ARG;
     const uint8_t *lv = reinterpret_cast<const uint8_t *>(levels);
-    if (blocks > 0) {
-        hipLaunchKernelGGL(compact_count_kernel, dim3((unsigned)blocks), dim3(kCompactBlock), 0, s, lv, d, counts);
-        if (launched() != GQ_OK) return GQ_ERR_DEVICE;
-    }
-    hipLaunchKernelGGL(compact_scan_kernel, dim3(1), dim3(kScanBlock), 0, s, counts, blocks, count_out);
+    // the scan's words and the count start from zero (a fill kernel, so that the call can be captured in a graph)
+    const int64_t words = 2 + blocks + (blocks + kGroupBlocks - 1) / kGroupBlocks;
+    hipLaunchKernelGGL(compact_clear_kernel, dim3((unsigned)((words + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, state, words, count_out);
     if (launched() != GQ_OK) return GQ_ERR_DEVICE;
     if (blocks > 0) {
-        hipLaunchKernelGGL(compact_write_kernel, dim3((unsigned)blocks), dim3(kCompactBlock), 0, s, lv, d, counts,
-                           indices_out, values_out, capacity);
+        hipLaunchKernelGGL(compact_onepass_kernel, dim3((unsigned)blocks), dim3(kCompactBlock), 0, s, lv, d, state, blocks,
+                           indices_out, values_out, capacity, count_out);
         if (launched() != GQ_OK) return GQ_ERR_DEVICE;
     }
     return GQ_OK;

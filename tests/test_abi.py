@@ -180,7 +180,7 @@ def test_argument_checks_need_no_device(gq):
     assert lib.gq_avg_reduce(arr, 2, 16, C.byref(P(gq.GQ_LINEAR, 8, gq.GQ_PACK_I4)), 0, fake, fake, None, None) == gq.GQ_ERR_UNSUPPORTED
     # sparse branch
     assert gq.compact_workspace_bytes(-1) == 0 and gq.compact_workspace_bytes(1 << 33) == 0
-    assert gq.compact_workspace_bytes(0) == 4 and gq.compact_workspace_bytes(16384) == 4 and gq.compact_workspace_bytes(16385) == 8
+    assert gq.compact_workspace_bytes(0) == 16 and gq.compact_workspace_bytes(32768) == 32 and gq.compact_workspace_bytes(32769) == 40
     cp = lambda p, lv=fake, d=64, cap=16, cnt=fake, ws=fake, wsb=1024: lib.gq_compact(lv, d, C.byref(p), fake, fake, cap, cnt, ws, wsb, None)
     assert cp(av) == gq.GQ_ERR_UNSUPPORTED and cp(ok, lv=odd) == I and cp(ok, d=-1) == I and cp(ok, d=1 << 33) == I
     assert cp(ok, cap=-1) == I and cp(ok, cnt=None) == I and cp(ok, cnt=odd) == I

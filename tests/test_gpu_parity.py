@@ -747,7 +747,7 @@ def test_compact_errors():
         gq.compact(big, 1 << 20, gq.make_params(0, 127), idx, val, cnt, workspace=torch.zeros(8, dtype=torch.uint8, device=DEV))
     assert e.value.status == gq.GQ_ERR_WORKSPACE
     assert gq.compact_workspace_bytes(-1) == 0 and gq.compact_workspace_bytes(1 << 33) == 0
-    assert gq.compact_workspace_bytes(0) == 4 and gq.compact_workspace_bytes(16385) == 8
+    assert gq.compact_workspace_bytes(0) == 16 and gq.compact_workspace_bytes(32769) == 40
     gq.compact(lv, 0, gq.make_params(0, 127), idx, val, cnt)                # d = 0: count 0
     torch.cuda.synchronize()
     assert int(cnt.item()) == 0

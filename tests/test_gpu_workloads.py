@@ -235,7 +235,7 @@ def compact_with_guard(lv, d, p, ws):
 @pytest.mark.parametrize("kind", ["linf", "l2"])
 def test_workload_c3_sparse_branch_at_full_size(kind):
     # Algorithm 1's sparse branch at the scored shape (d = 110e6, K = 16, linear s = 127, int8 codes): the block
-    # counts of one worker (6714 of them) take seven rounds of the scan, which smaller inputs never reach.
+    # scan runs over the 3357 spans of one worker, far more than are resident at once, which smaller inputs never reach.
     # Max norm: about 16 % of the codes are non-zero; L2 norm: about 0.05 % (the regime of Theorem 1).
     cfg = SI.CONFIGS["c3"]
     K, d, s = cfg["K"], cfg["d"], cfg["s"]
@@ -249,9 +249,9 @@ def test_workload_c3_sparse_branch_at_full_size(kind):
     dense = torch.empty(d, dtype=torch.int32, device=DEV)
     gq.int_aggregate(lvs, None, d, p, dense)
     ws = torch.empty(gq.compact_workspace_bytes(d), dtype=torch.uint8, device=DEV)
-    assert gq.compact_workspace_bytes(d) == 4 * 6714
+    assert gq.compact_workspace_bytes(d) == 8 * (2 + 3357 + 53)
     idxs, vals, cnts, total = [], [], [], 0
-    windows = spans(d, 33, edges=[1024 * 16384 * r for r in range(1, 7)])       # the scan's round boundaries too
+    windows = spans(d, 33, edges=[1024 * 16384 * r for r in range(1, 7)])
     for i in range(K):
         n, idx, val, cnt = compact_with_guard(lvs[i], d, p, ws)
         idxs.append(idx[:n]); vals.append(val[:n]); cnts.append(cnt); total += n
@@ -298,7 +298,7 @@ def test_workload_c3_sparse_branch_at_full_size(kind):
 
 def test_sparse_branch_with_32_bit_indices_up_to_the_limit():
     # d = 2^32 - 1, the largest gradient the sparse branch takes: coordinate indices use all 32 bits, the scan
-    # of 262144 block counts runs 256 rounds.  Two mostly-zero code vectors are built from seeded positions,
+    # runs over 131072 spans.  Two mostly-zero code vectors are built from seeded positions,
     # so the expected lists are the construction itself (sorted positions and their codes); the oracle's
     # compaction and receiver are run on windows of the same vectors.
     torch.cuda.empty_cache()
@@ -306,7 +306,7 @@ def test_sparse_branch_with_32_bit_indices_up_to_the_limit():
     free, _ = torch.cuda.mem_get_info()
     if free < 60 * (1 << 30):
         pytest.skip("needs 60 GB of free device memory")
-    assert gq.compact_workspace_bytes(d) == 4 * 262144 and gq.compact_workspace_bytes(d + 1) == 0
+    assert gq.compact_workspace_bytes(d) == 8 * (2 + 131072 + 2048) and gq.compact_workspace_bytes(d + 1) == 0
     rng = np.random.default_rng(2032)
     half = 1 << 31
     special = np.array([0, 1, 15, 16, 16383, 16384, 65535, 65536, half - 1, half, half + 1, d - 2, d - 1,
