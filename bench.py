@@ -51,6 +51,9 @@ def parse():
                     help="with --per-bucket-norm: the headline ms_per_step is the two-stream schedule (default: serial)")
     ap.add_argument("--no-window-ab", action="store_true",
                     help="skip the interleaved timing of the fused call with its write windows forced off and on")
+    ap.add_argument("--windows", default="default", choices=["default", "on", "off"],
+                    help="write windows of the fused call in the timed steps: the library's policy, forced on, or forced off "
+                         "(gq_params.flags); for profiling one variant at a time")
     ap.add_argument("--ab-rounds", type=int, default=15, help="rounds of the write-window A/B (each times off, then on)")
     ap.add_argument("--graph", action="store_true",
                     help="also capture the step in a HIP graph and time its replays (reported as graph_replay_ms_per_step)")
@@ -209,7 +212,8 @@ def main():
     K, d, s = cfg["K"], cfg["d"], cfg["s"]
     scheme = gq.GQ_LINEAR if cfg["scheme"] == "linear" else gq.GQ_EXP
     kind = {"linf": gq.GQ_NORM_LINF, "l2": gq.GQ_NORM_L2}[cfg["norm"]]
-    params = gq.make_params(scheme, s, gq.GQ_PACK_I8, gq.GQ_AGG_I32, seed=SI.QUANT_SEED)
+    win_flags = {"default": 0, "on": gq.GQ_FLAG_WRITE_WINDOWS_ON, "off": gq.GQ_FLAG_WRITE_WINDOWS_OFF}[args.windows]
+    params = gq.make_params(scheme, s, gq.GQ_PACK_I8, gq.GQ_AGG_I32, seed=SI.QUANT_SEED, flags=win_flags)
 
     xs = SI.make_workers(args.workload, device=dev)
     norm = torch.zeros(1, device=dev)
@@ -315,7 +319,7 @@ def main():
         windows_ab = {"windows_off_ms": float(np.mean(t_off)), "windows_on_ms": float(np.mean(t_on)),
                       "windows_off_median_ms": float(np.median(t_off)), "windows_on_median_ms": float(np.median(t_on)),
                       "rounds": args.ab_rounds,
-                      "headline_used": "windows_on" if by_policy else "windows_off",
+                      "headline_used": ("windows_" + args.windows) if args.windows != "default" else ("windows_on" if by_policy else "windows_off"),
                       "note": "interleaved off/on calls after the timed steps; the headline is the library's default policy"}
 
     traffic = valu_busy = traffic_note = None

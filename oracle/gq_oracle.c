@@ -46,6 +46,9 @@
  *                So k = h+1 exactly when U' < frac part, which has probability y*s - h as Eq. (2)
  *                asks, up to the binary32 granularity of U' and of v (a coordinate that sits on
  *                level k stays there with probability >= 1 - k*2^-23, with certainty for k <= 1).
+ *                |x| >= norm (y = 1, the coordinate the max norm is taken from) is the top level with
+ *                certainty: Eq. (2) keeps a value that sits on a level, and y = 1 is the one non-zero level
+ *                that binary32 can recognise exactly, since |x| * fl32(s/norm) need not equal s.
  *       exp:     z = fl32(|x| * scale), scale = fl32(2^(s-1) / norm), clamped to 2^(s-1);  R = r >> 9.
  *                z >= 1: z = 2^e * (1 + m/2^23); round up iff m + R >= 2^23: probability m/2^23 =
  *                (z - 2^e)/2^e exactly as Eq. (2) asks.   z < 1: m = z*2^23 rounded to nearest
@@ -82,7 +85,7 @@
  *   - sparse branch (Algorithm 1 says only that the non-zero values are all-gathered): a worker's message
  *     is the list of (coordinate index, signed code) of its non-zero codes in increasing index order, and the
  *     receiver adds the integer values of all K lists into a dense sum, which equals the dense aggregate.
- *   - top of the range: |x| = norm can land one ulp above s after rounding; the code is clamped to s.
+ *   - top of the range: |x| >= norm is the top level (both grids); below it the code is clamped to s.
  *   - norm == 0, norm not finite, or scale not finite: every code is 0.
  *
  * Floating point: the two decisions that turn a float into an integer (ceil(v), the carry out of
@@ -204,9 +207,10 @@ int gqo_global_norm(const float *const *x, int K, int64_t d, int kind, double *n
  * ------------------------------------------------------------------------------------------ */
 int32_t gqo_linear_code(float x, float norm, int s, uint32_t r)
 {
-    if (!(norm > 0.0f)) return 0;
+    if (!(norm > 0.0f) || !(norm <= FLT_MAX)) return 0;  /* zero, negative, NaN or infinite norm: every code is 0 */
     float scale = (float)s / norm;
     if (!(scale <= FLT_MAX)) return 0;
+    if (fabsf(x) >= norm) return (x < 0.0f) ? -s : s;   /* y = 1 = l_0: Eq. (2) leaves a value on a level there */
     float u = (float)r * 0x1.fffffep-33f;          /* U' in [0,1): fl32(r) times the largest float below 2^-32 */
     float v = fmaf(fabsf(x), scale, -u);           /* t - U' with one rounding */
     if (v != v) return 0;
@@ -222,13 +226,13 @@ int32_t gqo_linear_code(float x, float norm, int s, uint32_t r)
  * ------------------------------------------------------------------------------------------ */
 int32_t gqo_exp_code(float x, float norm, int s, uint32_t r)
 {
-    if (!(norm > 0.0f)) return 0;
+    if (!(norm > 0.0f) || !(norm <= FLT_MAX)) return 0;  /* zero, negative, NaN or infinite norm: every code is 0 */
     float top = ldexpf(1.0f, s - 1);
     float scale = top / norm;
     if (!(scale <= FLT_MAX)) return 0;
     float z = fabsf(x) * scale;
     if (z != z) return 0;
-    if (z > top) z = top;
+    if (z > top || fabsf(x) >= norm) z = top;     /* y = 1 = l_0 is on the grid whatever the rounding of the scale */
     uint32_t R = r >> 9;                            /* 23 dither bits */
     int32_t k;
     if (z >= 1.0f) {

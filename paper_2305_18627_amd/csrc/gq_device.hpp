@@ -66,6 +66,7 @@ __device__ __forceinline__ Words4 random_words(uint64_t seed, uint32_t worker, u
 struct Scale {
     float scale;   // s / norm (linear) or 2^(s-1) / norm (exponential); 0 if the norm is unusable
     float top;     // s (linear) or 2^(s-1) (exponential) as a float
+    float full;    // the norm: |x| >= full is y = 1, the top level with certainty; NaN (never reached) if the norm is unusable
 };
 
 template <int SCHEME>
@@ -74,8 +75,9 @@ __device__ __forceinline__ Scale make_scale(float norm, int s)
     Scale sc;
     sc.top = SCHEME == 0 ? (float)s : __uint_as_float((uint32_t)(127 + s - 1) << 23);
     const float q = sc.top / norm;                          // correctly rounded division
-    const bool ok = (norm > 0.0f) && (q <= 3.402823466e+38f);
+    const bool ok = (norm > 0.0f) && (norm <= 3.402823466e+38f) && (q <= 3.402823466e+38f);
     sc.scale = ok ? q : 0.0f;                               // zero / non-finite norm => every code is 0
+    sc.full = ok ? norm : __builtin_nanf("");
     return sc;
 }
 
@@ -98,9 +100,10 @@ template <> struct Round<0> {
     static __device__ __forceinline__ float value(float x, const Scale &sc, uint32_t r)
     {
         const float u = (float)r * 0x1.fffffep-33f;                       // U' in [0,1)
-        const float v = __builtin_fmaf(__builtin_fabsf(x), sc.scale, -u); // t - U', one rounding
+        const float ax = __builtin_fabsf(x);
+        const float v = __builtin_fmaf(ax, sc.scale, -u);                 // t - U', one rounding
         const float c = clamp_nan_to_zero(__builtin_ceilf(v), sc.top);   // clamp at the top level
-        return __builtin_copysignf(c, x);
+        return __builtin_copysignf(ax >= sc.full ? sc.top : c, x);       // y = 1 sits on the top level
     }
     static __device__ __forceinline__ int code_of_value(float value) { return (int)value; }
     static __device__ __forceinline__ int code(float x, const Scale &sc, uint32_t r) { return (int)value(x, sc, r); }
@@ -111,7 +114,8 @@ template <> struct Round<0> {
 template <> struct Round<1> {
     static __device__ __forceinline__ float value(float x, const Scale &sc, uint32_t r)
     {
-        const float z = clamp_nan_to_zero(__builtin_fabsf(x) * sc.scale, sc.top);
+        const float ax = __builtin_fabsf(x);
+        const float z = ax >= sc.full ? sc.top : clamp_nan_to_zero(ax * sc.scale, sc.top);   // y = 1 sits on the top level
         const float one = z < 1.0f ? 1.0f : 0.0f;
         const float w = z + one;
         const uint32_t b = __float_as_uint(w) + (r >> 9);
@@ -129,7 +133,8 @@ template <> struct Round<1> {
     // k = E - 126 for z >= 1 (value 2^(E-127)), k = E - 127 for z < 1 (value 0 or 1).
     static __device__ __forceinline__ int code(float x, const Scale &sc, uint32_t r)
     {
-        const float z = clamp_nan_to_zero(__builtin_fabsf(x) * sc.scale, sc.top);
+        const float ax = __builtin_fabsf(x);
+        const float z = ax >= sc.full ? sc.top : clamp_nan_to_zero(ax * sc.scale, sc.top);   // y = 1 sits on the top level
         const bool small = z < 1.0f;
         const float w = z + (small ? 1.0f : 0.0f);
         const uint32_t b = __float_as_uint(w) + (r >> 9);
