@@ -39,14 +39,15 @@
  *   exponential  z = min(fl32(|x| * fl32(2^(s-1)/norm)), 2^(s-1));  R = r >> 9;
  *                z >= 1: round the binary32 z up to the next power of two iff mantissa + R >= 2^23;
  *                z <  1: k = 1 iff rne(z * 2^23) + R >= 2^23, else 0
+ *   both grids   |x| >= norm (y = 1, e.g. the coordinate a max norm is taken from) is the top level k = s with certainty
  * Short draws (rng_bits = 16): one Philox call serves the eight coordinates 8c .. 8c+7, counter
  * (lo32(g/8), hi32(g/8), worker, 0); coordinate g takes the low (g even) or high (g odd) half of word
  * (g mod 8) / 2 as the TOP half of r, zeros below, and the two rules apply unchanged: the probability
  * of Eq. (2) is then met to 2^-16 and the generator costs half as much per coordinate.  index_base
  * must then be a multiple of 8.  Only gq_quantize and gq_fused_quantize_aggregate draw from this
  * stream; the other calls ignore rng_bits.
- * A norm that is zero or not finite (or so small that the scale overflows) gives all-zero codes.
- * Inputs must be finite with |x| <= norm; otherwise codes stay within [-s, s] but are unspecified.
+ * A norm that is zero, negative or not finite (or so small that the scale overflows) gives all-zero codes, also at
+ * NaN or Inf coordinates.  Under a usable norm a NaN coordinate gives code 0 and |x| > norm the top level.
  */
 #ifndef GQSGD_H
 #define GQSGD_H
