@@ -19,11 +19,13 @@ namespace gq {
 // words are consumed as they arrive.  A node's bits are the top s bits of a field of W = 8, 16 or 32 bits
 // (s <= 8, 16, 31) of the Philox call of its group of 32 / W nodes, so one call serves 4, 2 or 1 nodes.
 //
-// Two arithmetic paths give the same results.  For s <= 16 a partial result is held as the binary32 number
-// sign * 2^j it stands for (scaled by 2^(s + log2(n') + 1), so j = s + log2(n') + 1 - e >= 1, zero is 0.0f):
-// the sum of two of them is exact in binary32 (exponents at most 21 apart), and the random rounding to a
-// neighbouring power of two is an integer add on its mantissa followed by a mask, as in the exponential
-// quantiser.  For s > 16 (32-bit fields) the integer form of the listing is kept.
+// Three arithmetic paths give the same results.  For s <= 16 a partial result is held as the floating-point
+// number sign * 2^j it stands for (scaled by 2^(s + log2(n') + 1), so j = s + log2(n') + 1 - e >= 1, zero is 0):
+// the sum of two of them is exact (or rounds to the larger operand where the cap on k forbids any move anyway),
+// and the random rounding to a neighbouring power of two is an integer add on its mantissa followed by a mask,
+// as in the exponential quantiser.  s <= 8 (8-bit fields) runs on packed binary16 pairs, two coordinates per
+// instruction (exp_reduce_f16_kernel); 8 < s <= 16 on binary32; for s > 16 (32-bit fields) the integer form
+// of the listing is kept.
 // =============================================================================================
 constexpr int kReduceBlock = 128;
 
@@ -41,6 +43,25 @@ __device__ __forceinline__ float alg2_pair_f32(float x1, float x2, uint32_t A)
     const uint32_t opposite = (uint32_t)((int)(__float_as_uint(x1) ^ __float_as_uint(x2)) >> 31);   // all ones iff the signs differ
     const uint32_t R = A ^ (opposite & 0x7FFFFFu);
     return __uint_as_float((__float_as_uint(sum) + R) & 0xFF800000u);
+}
+
+// ---- packed binary16 path (8-bit fields, s <= 8) -------------------------------------------------------------
+// Two coordinates per register: x1, x2 hold two binary16 numbers sign * 2^j or 0 (j <= s + log2(n') + 1 <= 15).
+// The same construction on the 10-bit mantissa: A = (2^s - 1 - r) << (10 - s) in each half.  The binary16 sum is
+// exact up to a gap of 10 (same signs) or 11 (opposite signs); beyond that it rounds to the larger operand,
+// which is what the cap k <= m = s + 1 <= 9 asks for at those gaps anyway (the result never moves there).
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef short i16x2 __attribute__((ext_vector_type(2)));
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ f16x2 alg2_pair_f16x2(f16x2 x1, f16x2 x2, uint32_t A)
+{
+    const f16x2 sum = x1 + x2;
+    const uint32_t differ = __builtin_bit_cast(uint32_t, x1) ^ __builtin_bit_cast(uint32_t, x2);
+    const i16x2 opposite = __builtin_bit_cast(i16x2, differ) >> (i16x2){15, 15};                     // all ones per half iff the signs differ
+    const uint32_t R = A ^ (__builtin_bit_cast(uint32_t, opposite) & 0x03FF03FFu);
+    const u16x2 rounded = __builtin_bit_cast(u16x2, sum) + __builtin_bit_cast(u16x2, R);             // no carry between the halves
+    return __builtin_bit_cast(f16x2, __builtin_bit_cast(uint32_t, rounded) & 0xFC00FC00u);
 }
 
 // ---- integer path (32-bit fields) -------------------------------------------------------------------------
@@ -216,6 +237,121 @@ exp_reduce_kernel(LevelCPtrs Lv, int K, int64_t d, int s, uint64_t seed, uint64_
     }
 }
 
+// Algorithm 2 for s <= 8 on packed binary16 pairs: the same walk as exp_reduce_kernel with two coordinates per
+// register, which halves the instructions of the pair reductions (they dominate the kernel's time).
+template <int NPAD, bool UNIFORM_HI>
+__global__ void __launch_bounds__(kReduceBlock)
+exp_reduce_f16_kernel(LevelCPtrs Lv, int K, int64_t d, int s, uint64_t seed, uint64_t call_base,
+                      const float *__restrict__ norm, void *__restrict__ reduced_out, float *__restrict__ deq_out)
+{
+    constexpr int L = NPAD == 1 ? 0 : NPAD == 2 ? 1 : NPAD == 4 ? 2 : NPAD == 8 ? 3 : NPAD == 16 ? 4 : NPAD == 32 ? 5 : 6;
+    constexpr int PER = 4;                                   // tree nodes served by one Philox call (8-bit fields)
+    // the binary16 value sign * 2^min(|q|, s) of every code byte q (0 for q = 0)
+    __shared__ _Float16 leaf_value[256];
+    for (int b = threadIdx.x; b < 256; b += kReduceBlock) {
+        const int q = (int)(int8_t)b;
+        const uint16_t bits = q ? (uint16_t)(((15 + min(abs(q), s)) << 10) | (q < 0 ? 0x8000 : 0)) : (uint16_t)0;
+        leaf_value[b] = __builtin_bit_cast(_Float16, bits);
+    }
+    __syncthreads();
+    const int64_t v = (int64_t)blockIdx.x * kReduceBlock + threadIdx.x;
+    const int64_t nfull = d >> 2;
+    const int nvalid = v < nfull ? 4 : (v == nfull ? (int)(d & 3) : 0);
+    if (nvalid == 0) return;
+    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    uint32_t c_lo, c_hi;
+    if (UNIFORM_HI) {
+        c_hi = (uint32_t)(call_base >> 32);
+        c_lo = (uint32_t)call_base + (uint32_t)v;           // no carry (host)
+    } else {
+        const uint64_t call = call_base + (uint64_t)v;
+        c_lo = (uint32_t)call;
+        c_hi = (uint32_t)(call >> 32);
+    }
+    auto fetch = [&](int w) -> uint32_t {
+        if (w >= K) return 0u;                              // missing workers are zero leaves
+        if (nvalid == 4) return __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(Lv.lv[w]) + v);
+        const uint8_t *b = reinterpret_cast<const uint8_t *>(Lv.lv[w]) + (v << 2);
+        uint32_t t = 0;
+        for (int i = 0; i < nvalid; i++) t |= (uint32_t)b[i] << (8 * i);
+        return t;
+    };
+    // every byte of a complemented Philox word keeps its top s bits only: byte << 2 is then A of its half
+    const uint32_t keep = 0x01010101u * ((0xFFu << (8 - s)) & 0xFFu);
+    f16x2 st[L + 1][2];                                      // the stack: coordinates (0,1) and (2,3) of every partial result
+    uint32_t grp[L + 1][4];                                  // masked complemented Philox words of the node groups in use
+    constexpr int kBatch = NPAD < 8 ? NPAD : 8;
+#pragma unroll
+    for (int w0 = 0; w0 < NPAD; w0 += kBatch) {
+        uint32_t words[kBatch];
+#pragma unroll
+        for (int j = 0; j < kBatch; j++) words[j] = fetch(w0 + j);
+#pragma unroll
+        for (int j = 0; j < kBatch; j++) {
+            const int i = w0 + j;                            // leaf index; the stack depth is popcount(i)
+            int top = __builtin_popcount((unsigned)i);
+            st[top][0] = (f16x2){leaf_value[words[j] & 255u], leaf_value[(words[j] >> 8) & 255u]};
+            st[top][1] = (f16x2){leaf_value[(words[j] >> 16) & 255u], leaf_value[words[j] >> 24]};
+#pragma unroll
+            for (int lvl = 1; lvl <= L; lvl++) {
+                if (((i + 1) & ((1 << lvl) - 1)) == 0) {     // a subtree of 2^lvl leaves is complete
+                    const int node = (NPAD >> lvl) + (i >> lvl);            // heap numbering
+                    const int slot = (node == 1 && NPAD >= 4) ? lvl - 1 : lvl;   // the root shares its group with nodes 2 and 3
+                    if (first_of_group<NPAD, PER>(node)) {
+                        const Words4 r = philox4x32_10(c_lo, c_hi, (uint32_t)(node / PER), 1u, k0, k1);
+#pragma unroll
+                        for (int c = 0; c < 4; c++) grp[slot][c] = ~r.w[c] & keep;
+                    }
+                    // byte `node % 4` of the words of coordinates (0,1) resp. (2,3) into the low bytes of the two halves
+                    constexpr uint32_t kZero = 0x0Cu;        // v_perm_b32 selector of a zero byte
+                    const uint32_t sel = (kZero << 24) | ((uint32_t)(4 + node % PER) << 16) | (kZero << 8) | (uint32_t)(node % PER);
+                    const uint32_t A01 = __builtin_amdgcn_perm(grp[slot][1], grp[slot][0], sel) << 2;
+                    const uint32_t A23 = __builtin_amdgcn_perm(grp[slot][3], grp[slot][2], sel) << 2;
+                    st[top - 1][0] = alg2_pair_f16x2(st[top - 1][0], st[top][0], A01);
+                    st[top - 1][1] = alg2_pair_f16x2(st[top - 1][1], st[top][1], A23);
+                    top--;
+                }
+            }
+        }
+    }
+    int root[4];                                            // sign * e of the root, 0 for zero
+#pragma unroll
+    for (int c = 0; c < 4; c++) {
+        const uint32_t b = (__builtin_bit_cast(uint32_t, st[0][c >> 1]) >> (16 * (c & 1))) & 0xFFFFu;
+        const int j = (int)((b >> 10) & 31u) - 15;          // the root stands for 2^j, j = s + L + 1 - e
+        const int e = (b & 0x7C00u) ? s + L + 1 - j : 0;
+        root[c] = (b & 0x8000u) ? -e : e;
+    }
+    if (reduced_out) {
+        const uint32_t wout = (uint32_t)(root[0] & 255) | ((uint32_t)(root[1] & 255) << 8) |
+                              ((uint32_t)(root[2] & 255) << 16) | ((uint32_t)(root[3] & 255) << 24);
+        if (nvalid == 4) {
+            __builtin_nontemporal_store(wout, reinterpret_cast<uint32_t *>(reduced_out) + v);
+        } else {
+            uint8_t *b = reinterpret_cast<uint8_t *>(reduced_out) + (v << 2);
+            for (int i = 0; i < nvalid; i++) b[i] = (uint8_t)(wout >> (8 * i));
+        }
+    }
+    if (deq_out) {
+        // the mean the pair stands for: sign * 2^-e * (2 n') * norm / K
+        const float nrm = *norm;
+        const float c = (nrm > 0.0f && nrm <= 3.402823466e+38f) ? nrm / (float)K : 0.0f;
+        float o[4];
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const int se = root[i], e = abs(se);
+            const float p2 = __uint_as_float((uint32_t)(127 + 1 + L - e) << 23);     // 2^(1+L-e)
+            o[i] = e ? (se < 0 ? -(c * p2) : c * p2) : 0.0f;
+        }
+        if (nvalid == 4) {
+            const f32x4 t = {o[0], o[1], o[2], o[3]};
+            __builtin_nontemporal_store(t, reinterpret_cast<f32x4 *>(deq_out) + v);
+        } else {
+            for (int i = 0; i < nvalid; i++) deq_out[(v << 2) + i] = o[i];
+        }
+    }
+}
+
 // =============================================================================================
 // Implementation section: low-bit linear codes averaged inside every reduce step, so that they never leave their
 // b bits.  Same tree walk as exp_reduce_kernel; a node holds round((a + b) / 2), an odd sum going
@@ -364,7 +500,9 @@ gq_status gq_exp_reduce(const void *const *levels, int K, int64_t d, const gq_pa
     const int field_bits = p->s <= 8 ? 8 : (p->s <= 16 ? 16 : 32);
 #define GQ_RED3(N, UH, FB) hipLaunchKernelGGL((exp_reduce_kernel<N, UH, FB>), grid, block, 0, s, Lv, K, d, p->s, p->seed, \
                                               call_base, norm, reduced_out, dequant_out)
-#define GQ_RED2(N, UH) do { if (field_bits == 8) GQ_RED3(N, UH, 8); else if (field_bits == 16) GQ_RED3(N, UH, 16); else GQ_RED3(N, UH, 32); } while (0)
+#define GQ_RED16(N, UH) hipLaunchKernelGGL((exp_reduce_f16_kernel<N, UH>), grid, block, 0, s, Lv, K, d, p->s, p->seed, \
+                                           call_base, norm, reduced_out, dequant_out)
+#define GQ_RED2(N, UH) do { if (field_bits == 8) GQ_RED16(N, UH); else if (field_bits == 16) GQ_RED3(N, UH, 16); else GQ_RED3(N, UH, 32); } while (0)
 #define GQ_RED(N) do { if (one_stretch) GQ_RED2(N, true); else GQ_RED2(N, false); } while (0)
     switch (npad) {
     case 1: GQ_RED(1); break;
@@ -378,6 +516,7 @@ gq_status gq_exp_reduce(const void *const *levels, int K, int64_t d, const gq_pa
 #undef GQ_RED
 #undef GQ_RED2
 #undef GQ_RED3
+#undef GQ_RED16
     return launched();
 }
 
