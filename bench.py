@@ -178,16 +178,19 @@ def time_rows(gq, torch, xs, norm, params, cfg, args):
         nnz = [int(c.item()) for c in cnts]
         idxs = [torch.empty(max(n, 1), dtype=torch.int32, device=dev) for n in nnz]
         vals = [torch.empty(max(n, 1), dtype=torch.int8, device=dev) for n in nnz]
+        tabs = [torch.empty(gq.tile_starts_len(d), dtype=torch.int32, device=dev) for _ in range(K)]
 
         def compact_all():
             for i in range(K):
-                gq.compact(lvs[i], d, p, idxs[i], vals[i], cnts[i], ws)
+                gq.compact(lvs[i], d, p, idxs[i], vals[i], cnts[i], ws, tile_starts_out=tabs[i])
 
         tot = float(sum(nnz))
         # the method's bytes: every code read once, every pair (4-byte index + 1-byte code) written once
         rows["compact_xK"] = timed(compact_all, 1.0 * K * d + 5.0 * tot)
         if aggf == gq.GQ_AGG_I32:
-            rows["sparse_aggregate"] = timed(lambda: gq.sparse_aggregate(idxs, vals, cnts, d, p, agg), 4.0 * d + 5.0 * tot)
+            # with the senders' tables of tile starts, and without them (the receiver then searches the lists)
+            rows["sparse_aggregate"] = timed(lambda: gq.sparse_aggregate(idxs, vals, cnts, d, p, agg, tile_starts=tabs), 4.0 * d + 5.0 * tot)
+            rows["sparse_aggregate_searching"] = timed(lambda: gq.sparse_aggregate(idxs, vals, cnts, d, p, agg), 4.0 * d + 5.0 * tot)
         rows["nonzero_fraction"] = tot / (float(K) * d)
     rows["formats"] = {"pack": cfg["pack"], "agg": cfg["agg"]}
     return rows

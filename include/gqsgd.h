@@ -255,14 +255,19 @@ gq_status gq_avg_reduce(const void *const *levels /* host */, int K, int64_t d, 
  *   indices_out      device uint32[capacity]; values_out device int8[capacity]
  *   count_out        device uint64[1]: the TRUE number of non-zero codes; if it exceeds `capacity` only the
  *                    first `capacity` pairs were written and the caller must retry with larger buffers
+ *   tile_starts_out  device uint32[gq_tile_starts_len(d)] or NULL: entry t = the number of non-zero codes with index
+ *                    below 4096 * t, i.e. where coordinates 4096 t .. 4096 t + 4095 begin in the list; the last
+ *                    entry (t = ceil(d / 4096)) is the count.  A small table (4 bytes per 4096 coordinates) that
+ *                    travels with the list and spares the receiver every search.
  *   workspace        device scratch of at least gq_compact_workspace_bytes(d) bytes, 8-byte aligned, overwritten (the
  *                    words of a scan over spans of 32768 codes); not to be shared by calls that may overlap
  * The codes are read once and only the list is written.  The result is unique (sorted by index) and does not
  * depend on scheduling.  count_out = 2^64 - 1 reports that the scan over the blocks gave up waiting (it cannot
  * in a working launch: every block waits only for blocks that started before it); the lists are then incomplete. */
 size_t gq_compact_workspace_bytes(int64_t d);
+int64_t gq_tile_starts_len(int64_t d);          /* ceil(d / 4096) + 1; 0 if d is out of range */
 gq_status gq_compact(const void *levels, int64_t d, const gq_params *p /* host */, uint32_t *indices_out,
-                     int8_t *values_out, int64_t capacity, uint64_t *count_out,
+                     int8_t *values_out, int64_t capacity, uint64_t *count_out, uint32_t *tile_starts_out,
                      void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Receiver side of the sparse branch: the dense integer sum A_j of the K workers' lists, equal to what
@@ -270,11 +275,14 @@ gq_status gq_compact(const void *levels, int64_t d, const gq_params *p /* host *
  *   indices, values  host arrays of K device lists as written by gq_compact (indices strictly increasing)
  *   counts           host array of K device uint64[1] (read on the device; min(count, capacity) entries are used)
  *   capacities       host array of K list capacities
+ *   tile_starts      host array of K device tables as written by gq_compact for the same d, or NULL (the array, or
+ *                    single entries of it): without a table the receiver locates its tiles by binary search
  *   agg_out          device int32[d] (p->agg must be GQ_AGG_I32), fully overwritten
  * Entries whose index is not below d are ignored.  Returns GQ_ERR_OVERFLOW if gq_check_width(p, K) fails. */
 gq_status gq_sparse_aggregate(const uint32_t *const *indices /* host */, const int8_t *const *values /* host */,
                               const uint64_t *const *counts /* host */, const int64_t *capacities /* host */,
-                              int K, int64_t d, const gq_params *p /* host */, void *agg_out, void *hip_stream);
+                              const uint32_t *const *tile_starts /* host */, int K, int64_t d,
+                              const gq_params *p /* host */, void *agg_out, void *hip_stream);
 
 #ifdef __cplusplus
 }

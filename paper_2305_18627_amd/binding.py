@@ -23,7 +23,7 @@ GQ_FLAG_WRITE_WINDOWS_OFF, GQ_FLAG_WRITE_WINDOWS_ON = 1, 2
 # every symbol include/gqsgd.h declares
 EXPORTS = ("gq_version", "gq_status_string", "gq_check_width", "gq_norm_workspace_bytes", "gq_global_norm",
            "gq_global_norm_static", "gq_bucketed_workspace_bytes", "gq_bucketed_quantize_aggregate",
-           "gq_quantize", "gq_int_aggregate", "gq_dequantize", "gq_fused_quantize_aggregate", "gq_exp_reduce", "gq_avg_reduce", "gq_compact_workspace_bytes", "gq_compact",
+           "gq_quantize", "gq_int_aggregate", "gq_dequantize", "gq_fused_quantize_aggregate", "gq_exp_reduce", "gq_avg_reduce", "gq_compact_workspace_bytes", "gq_tile_starts_len", "gq_compact",
            "gq_sparse_aggregate")
 
 
@@ -61,8 +61,9 @@ def _load():
         "gq_exp_reduce": (i32, [C.POINTER(vp), i32, i64, pp, i64, vp, vp, vp, vp]),
         "gq_avg_reduce": (i32, [C.POINTER(vp), i32, i64, pp, i64, vp, vp, vp, vp]),
         "gq_compact_workspace_bytes": (sz, [i64]),
-        "gq_compact": (i32, [vp, i64, pp, vp, vp, i64, vp, vp, sz, vp]),
-        "gq_sparse_aggregate": (i32, [C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(i64), i32, i64, pp, vp, vp]),
+        "gq_tile_starts_len": (i64, [i64]),
+        "gq_compact": (i32, [vp, i64, pp, vp, vp, i64, vp, vp, vp, sz, vp]),
+        "gq_sparse_aggregate": (i32, [C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(i64), C.POINTER(vp), i32, i64, pp, vp, vp]),
         "gq_fused_quantize_aggregate": (i32, [C.POINTER(vp), i32, i64, vp, pp, i64, vp, vp, C.POINTER(vp),
                                                C.POINTER(vp), vp]),
     }
@@ -266,24 +267,34 @@ def compact_workspace_bytes(d):
     return int(_lib.gq_compact_workspace_bytes(int(d)))
 
 
-def compact(levels, d, params, indices_out, values_out, count_out, workspace=None, stream=None):
-    """gq_compact: the non-zero int8 codes of one worker as (index, code) pairs.  Returns the workspace used."""
+def tile_starts_len(d):
+    return int(_lib.gq_tile_starts_len(int(d)))
+
+
+def compact(levels, d, params, indices_out, values_out, count_out, workspace=None, stream=None, tile_starts_out=None):
+    """gq_compact: the non-zero int8 codes of one worker as (index, code) pairs, and optionally the table of where
+    every tile of 4096 coordinates begins in the list.  Returns the workspace used."""
     _need(levels, int(d), "levels"); _need(count_out, 8, "count_out")
     _need(values_out, indices_out.numel(), "values_out"); _need(indices_out, 0, "indices_out")
+    _need(tile_starts_out, 4 * tile_starts_len(d), "tile_starts_out")
     if workspace is None:
         workspace = torch.empty(compact_workspace_bytes(d), dtype=torch.uint8, device=count_out.device)
     st = _lib.gq_compact(_ptr(levels), int(d), C.byref(params), _ptr(indices_out), _ptr(values_out),
-                         indices_out.numel(), _ptr(count_out), _ptr(workspace),
+                         indices_out.numel(), _ptr(count_out), _ptr(tile_starts_out), _ptr(workspace),
                          workspace.numel() * workspace.element_size(), _stream(stream))
     _check(st, "gq_compact")
     return workspace
 
 
-def sparse_aggregate(indices, values, counts, d, params, agg_out, stream=None):
+def sparse_aggregate(indices, values, counts, d, params, agg_out, stream=None, tile_starts=None):
     for i, v, c in zip(indices, values, counts):
         _need(i, 0, "indices"); _need(v, i.numel(), "values"); _need(c, 8, "count")
+    if tile_starts is not None:
+        for t in tile_starts:
+            _need(t, 4 * tile_starts_len(d), "tile_starts")
     _need(agg_out, 4 * int(d), "agg_out")
     caps = (C.c_int64 * len(indices))(*[t.numel() for t in indices])
-    st = _lib.gq_sparse_aggregate(_ptr_array(indices), _ptr_array(values), _ptr_array(counts), caps, len(indices),
+    starts = None if tile_starts is None else (C.c_void_p * len(tile_starts))(*[t.data_ptr() if t is not None else None for t in tile_starts])
+    st = _lib.gq_sparse_aggregate(_ptr_array(indices), _ptr_array(values), _ptr_array(counts), caps, starts, len(indices),
                                   int(d), C.byref(params), _ptr(agg_out), _stream(stream))
     _check(st, "gq_sparse_aggregate")

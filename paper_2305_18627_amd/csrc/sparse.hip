@@ -94,11 +94,14 @@ constexpr uint64_t kPublished = 1ull << 32;
 constexpr uint64_t kGroupPublished = 1ull << 40;
 constexpr int kPrefixMaxPolls = 1 << 21;
 
-__global__ void __launch_bounds__(kBlock) compact_clear_kernel(uint64_t *__restrict__ state, int64_t words, uint64_t *__restrict__ count_out)
+// `empty_starts`: the one entry of the table of tile starts of an empty gradient, or nullptr
+__global__ void __launch_bounds__(kBlock) compact_clear_kernel(uint64_t *__restrict__ state, int64_t words, uint64_t *__restrict__ count_out,
+                                                               uint32_t *__restrict__ empty_starts)
 {
     const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i < words) state[i] = 0;
     if (i == 0) *count_out = 0;
+    if (i == 0 && empty_starts) empty_starts[0] = 0;
 }
 
 __device__ __forceinline__ uint64_t state_load(const uint64_t *p)
@@ -187,7 +190,7 @@ __device__ __forceinline__ void block_scan_tiles(const uint32_t *cnt, uint32_t *
 __global__ void __launch_bounds__(kCompactBlock)
 compact_onepass_kernel(const uint8_t *__restrict__ lv, int64_t d, uint64_t *__restrict__ state, int64_t nspans,
                        uint32_t *__restrict__ indices_out, int8_t *__restrict__ values_out, int64_t capacity,
-                       uint64_t *__restrict__ count_out)
+                       uint64_t *__restrict__ count_out, uint32_t *__restrict__ tile_starts_out)
 {
     __shared__ uint32_t sh[(kCompactBlock / 64) * (kCompactTiles / 2)];
     __shared__ uint32_t s_idx[kCompactTile];
@@ -265,6 +268,19 @@ compact_onepass_kernel(const uint8_t *__restrict__ lv, int64_t d, uint64_t *__re
             __syncthreads();
             base = s_base;
             if (base < 0) return;                            // uniform over the block
+            if (tile_starts_out) {
+                // where each tile of the span begins in the list (what the receiver would otherwise search for),
+                // and behind the last tile the end of the list
+                const int64_t ntiles = (d + kCompactTile - 1) / kCompactTile;
+                if (threadIdx.x < kCompactTiles) {
+                    uint32_t start = (uint32_t)base;
+#pragma unroll
+                    for (int jj = 0; jj < kCompactTiles; jj++) if (jj < (int)threadIdx.x) start += total[jj];
+                    const int64_t tile = span * kCompactTiles + threadIdx.x;
+                    if (tile < ntiles) tile_starts_out[tile] = start;
+                }
+                if (span == nspans - 1 && threadIdx.x == 0) tile_starts_out[ntiles] = (uint32_t)(base + span_total);
+            }
         } else {
             __syncthreads();
         }
@@ -283,81 +299,84 @@ struct SparseLists {
     const uint32_t *idx[kMaxWorkers];
     const int8_t *val[kMaxWorkers];
     const uint64_t *cnt[kMaxWorkers];
+    const uint32_t *starts[kMaxWorkers];     // where every tile of kSparseTile coordinates begins in the list, or nullptr
     int64_t cap[kMaxWorkers];
 };
 
-// Receiver side.  A block owns kSparseTiles consecutive tiles of kSparseTile coordinates.  It first finds, by
-// binary search in every worker's sorted index list, where each of its tile boundaries falls (all
-// K * (kSparseTiles + 1) searches run side by side, one per thread, so the block pays the latency of one
-// search).  Then, tile by tile, the workers' entries are added into an LDS copy of the tile (LDS atomics), the
-// threads being split evenly over the workers so that short lists are walked in parallel, and the tile is
-// written with 128-bit stores.  No global atomics and no separate zero fill: every output word is written
-// exactly once.
-constexpr int kSparseTile = 4096;
-constexpr int kSparseTiles = 4;
+// Receiver side.  A workgroup of 512 threads owns a span of 8192 coordinates, held as an int32 array in LDS.
+// The threads are split evenly over the K workers (512 / K' lanes each, K' = K rounded up to a power of two), so
+// that all K list segments of the span are walked side by side: every lane learns where its worker's segment begins
+// and ends -- from the table of tile starts that gq_compact wrote beside the list, or, if the sender gave none, by
+// binary search in the sorted index list -- and adds its share of the entries into the LDS array (LDS atomics),
+// four loads in flight per lane.  The span is then written once with 128-bit stores.  No global atomics and no
+// separate zero fill: every output word is written exactly once.
+constexpr int kSparseBlock = 512;
+constexpr int kSparseSpan = 2 * kCompactTile;            // two tiles of the sender's table of tile starts
 
 template <int SCHEME>
-__global__ void __launch_bounds__(kBlock)
-sparse_tile_kernel(SparseLists S, int K, int lanes_per_worker, int64_t d, int *__restrict__ agg)
+__global__ void __launch_bounds__(kSparseBlock)
+sparse_span_kernel(SparseLists S, int K, int lanes_per_worker, int64_t d, int *__restrict__ agg)
 {
-    __shared__ int tile[kSparseTile];
-    __shared__ int64_t bound[kMaxWorkers * (kSparseTiles + 1)];
-    const int64_t lo0 = (int64_t)blockIdx.x * (kSparseTile * kSparseTiles);
-    for (int b = threadIdx.x; b < K * (kSparseTiles + 1); b += kBlock) {
-        const int w = b / (kSparseTiles + 1), t = b - w * (kSparseTiles + 1);
-        const int64_t edge = lo0 + (int64_t)t * kSparseTile;
-        const int64_t key = edge < d ? edge : d;
-        const uint64_t have = *S.cnt[w];
-        const int64_t n = have < (uint64_t)S.cap[w] ? (int64_t)have : S.cap[w];
-        int64_t a = 0, e = n;                                  // first entry whose index is >= key
-        while (a < e) {
-            const int64_t mid = (a + e) >> 1;
-            if ((int64_t)S.idx[w][mid] < key) a = mid + 1; else e = mid;
-        }
-        bound[b] = a;
-    }
+    __shared__ int span[kSparseSpan];
+    __shared__ int64_t s_begin[kMaxWorkers], s_end[kMaxWorkers];
+    const int64_t lo = (int64_t)blockIdx.x * kSparseSpan;
+    const int64_t hi = lo + kSparseSpan < d ? lo + kSparseSpan : d;
     const int w = (int)threadIdx.x / lanes_per_worker;         // this thread's worker (if w < K) and its slot
     const int slot = (int)threadIdx.x - w * lanes_per_worker;
-#pragma unroll 1
-    for (int t = 0; t < kSparseTiles; t++) {
-        const int64_t lo = lo0 + (int64_t)t * kSparseTile;
-        if (lo >= d) break;                                     // uniform over the block
-        for (int i = threadIdx.x; i < kSparseTile; i += kBlock) tile[i] = 0;
-        __syncthreads();                                        // also orders the searches before their first use
-        auto add_entry = [&](int ww, int64_t e) {
-            const int64_t j = (int64_t)S.idx[ww][e] - lo;
-            const int q = S.val[ww][e];
-            int val = q;
+    // the worker's entries with lo <= index < hi lie at [begin, end) of its list: lane 0 of the worker's lanes looks up
+    // begin, lane 1 end (there are at least eight lanes per worker)
+    if (w < K && slot < 2) {
+        const uint64_t have = *S.cnt[w];
+        const int64_t n = have < (uint64_t)S.cap[w] ? (int64_t)have : S.cap[w];
+        const int64_t key = slot == 0 ? lo : hi;
+        int64_t at;
+        if (S.starts[w]) {
+            const int64_t ntiles = (d + kCompactTile - 1) / kCompactTile;
+            const int64_t t = (key + kCompactTile - 1) / kCompactTile;     // key is a multiple of the tile size, or d
+            at = (int64_t)S.starts[w][t < ntiles ? t : ntiles];
+            at = at < n ? at : n;                              // a list cut short by its capacity ends at n
+        } else {
+            int64_t a = 0, e = n;                              // first entry whose index is >= key
+            while (a < e) {
+                const int64_t mid = (a + e) >> 1;
+                if ((int64_t)S.idx[w][mid] < key) a = mid + 1; else e = mid;
+            }
+            at = a;
+        }
+        if (slot == 0) s_begin[w] = at; else s_end[w] = at;
+    }
+    for (int i = threadIdx.x * 4; i < kSparseSpan; i += kSparseBlock * 4) *reinterpret_cast<i32x4 *>(&span[i]) = i32x4{0, 0, 0, 0};
+    __syncthreads();
+    if (w < K) {
+        const int64_t begin = s_begin[w], end = s_end[w];
+        const uint32_t *idx = S.idx[w];
+        const int8_t *val = S.val[w];
+        auto add_entry = [&](uint32_t index, int q) {
+            int v = q;
             if (SCHEME == 1) {
                 const int mag = (int)((1u << abs(q)) >> 1);
-                val = q < 0 ? -mag : mag;
+                v = q < 0 ? -mag : mag;
             }
-            if (j >= 0 && j < kSparseTile) atomicAdd(&tile[j], val);   // always true for a sorted list
+            const int64_t j = (int64_t)index - lo;
+            if (j >= 0 && j < kSparseSpan) atomicAdd(&span[j], v);     // always true for a sorted list
         };
-        // long lists: the whole block walks one worker's entries at a time (1 KiB contiguous per wave and load);
-        // short lists: the threads are split over the workers, which are then walked side by side
-        int64_t entries = 0;
-        for (int ww = 0; ww < K; ww++) entries += bound[ww * (kSparseTiles + 1) + t + 1] - bound[ww * (kSparseTiles + 1) + t];
-        if (entries >= (int64_t)K * (kBlock / 2)) {             // uniform over the block
-            for (int ww = 0; ww < K; ww++) {
-                const int64_t end = bound[ww * (kSparseTiles + 1) + t + 1];
-                for (int64_t e = bound[ww * (kSparseTiles + 1) + t] + threadIdx.x; e < end; e += kBlock) add_entry(ww, e);
-            }
-        } else if (w < K) {
-            const int64_t end = bound[w * (kSparseTiles + 1) + t + 1];
-            for (int64_t e = bound[w * (kSparseTiles + 1) + t] + slot; e < end; e += lanes_per_worker) add_entry(w, e);
+        int64_t e = begin + slot;
+        const int64_t step = lanes_per_worker;
+        for (; e + 3 * step < end; e += 4 * step) {            // four entries in flight per lane
+            const uint32_t i0 = idx[e], i1 = idx[e + step], i2 = idx[e + 2 * step], i3 = idx[e + 3 * step];
+            const int q0 = val[e], q1 = val[e + step], q2 = val[e + 2 * step], q3 = val[e + 3 * step];
+            add_entry(i0, q0); add_entry(i1, q1); add_entry(i2, q2); add_entry(i3, q3);
         }
-        __syncthreads();
-        for (int i = threadIdx.x * 4; i < kSparseTile; i += kBlock * 4) {
-            const int64_t c = lo + i;
-            if (c + 4 <= d) {
-                const i32x4 o = {tile[i], tile[i + 1], tile[i + 2], tile[i + 3]};
-                __builtin_nontemporal_store(o, reinterpret_cast<i32x4 *>(agg + c));
-            } else {
-                for (int u = 0; u < 4 && c + u < d; u++) agg[c + u] = tile[i + u];
-            }
+        for (; e < end; e += step) add_entry(idx[e], val[e]);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x * 4; i < kSparseSpan; i += kSparseBlock * 4) {
+        const int64_t c = lo + i;
+        if (c + 4 <= d) {
+            __builtin_nontemporal_store(*reinterpret_cast<const i32x4 *>(&span[i]), reinterpret_cast<i32x4 *>(agg + c));
+        } else {
+            for (int u = 0; u < 4 && c + u < d; u++) agg[c + u] = span[i + u];
         }
-        __syncthreads();                                        // the tile is cleared again by the next round
     }
 }
 
@@ -375,8 +394,15 @@ size_t gq_compact_workspace_bytes(int64_t d)
     return (size_t)(2 + blocks + groups) * sizeof(uint64_t); // two spare words, a word per block and per group of 64
 }
 
+int64_t gq_tile_starts_len(int64_t d)
+{
+    if (d < 0 || d > 0xFFFFFFFFLL) return 0;
+    return (d + kCompactTile - 1) / kCompactTile + 1;
+}
+
 gq_status gq_compact(const void *levels, int64_t d, const gq_params *p, uint32_t *indices_out, int8_t *values_out,
-                     int64_t capacity, uint64_t *count_out, void *workspace, size_t workspace_bytes, void *hip_stream)
+                     int64_t capacity, uint64_t *count_out, uint32_t *tile_starts_out, void *workspace, size_t workspace_bytes,
+                     void *hip_stream)
 {
     const gq_status st = check_params(p, true, false);
     if (st != GQ_OK) return st;
@@ -385,6 +411,7 @@ gq_status gq_compact(const void *levels, int64_t d, const gq_params *p, uint32_t
     if (!aligned(count_out, 8)) return GQ_ERR_INVALID_ARG;
     if (d > 0 && !aligned(levels, 16)) return GQ_ERR_INVALID_ARG;
     if (capacity > 0 && (!aligned(indices_out, 4) || !values_out)) return GQ_ERR_INVALID_ARG;
+    if (tile_starts_out && !aligned(tile_starts_out, 4)) return GQ_ERR_INVALID_ARG;
     if (!workspace || workspace_bytes < gq_compact_workspace_bytes(d)) return GQ_ERR_WORKSPACE;
     if (!aligned(workspace, 8)) return GQ_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)hip_stream;
@@ -394,18 +421,20 @@ gq_status gq_compact(const void *levels, int64_t d, const gq_params *p, uint32_t
     const uint8_t *lv = reinterpret_cast<const uint8_t *>(levels);
     // the scan's words and the count start from zero (a fill kernel, so that the call can be captured in a graph)
     const int64_t words = 2 + blocks + (blocks + kGroupBlocks - 1) / kGroupBlocks;
-    hipLaunchKernelGGL(compact_clear_kernel, dim3((unsigned)((words + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, state, words, count_out);
+    hipLaunchKernelGGL(compact_clear_kernel, dim3((unsigned)((words + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, state, words, count_out,
+                       blocks == 0 ? tile_starts_out : nullptr);
     if (launched() != GQ_OK) return GQ_ERR_DEVICE;
     if (blocks > 0) {
         hipLaunchKernelGGL(compact_onepass_kernel, dim3((unsigned)blocks), dim3(kCompactBlock), 0, s, lv, d, state, blocks,
-                           indices_out, values_out, capacity, count_out);
+                           indices_out, values_out, capacity, count_out, tile_starts_out);
         if (launched() != GQ_OK) return GQ_ERR_DEVICE;
     }
     return GQ_OK;
 }
 
 gq_status gq_sparse_aggregate(const uint32_t *const *indices, const int8_t *const *values,
-                              const uint64_t *const *counts, const int64_t *capacities, int K, int64_t d,
+                              const uint64_t *const *counts, const int64_t *capacities,
+                              const uint32_t *const *tile_starts, int K, int64_t d,
                               const gq_params *p, void *agg_out, void *hip_stream)
 {
     gq_status st = check_params(p, false, true);
@@ -423,19 +452,20 @@ gq_status gq_sparse_aggregate(const uint32_t *const *indices, const int8_t *cons
         S.val[i] = values[i];
         S.cnt[i] = counts[i];
         S.cap[i] = capacities[i];
+        S.starts[i] = tile_starts ? tile_starts[i] : nullptr;
+        if (S.starts[i] && !aligned(S.starts[i], 4)) return GQ_ERR_INVALID_ARG;
     }
     if (d > 0 && !aligned(agg_out, 16)) return GQ_ERR_INVALID_ARG;
     if (d == 0) return GQ_OK;
     hipStream_t s = (hipStream_t)hip_stream;
-    const int64_t span = (int64_t)kSparseTile * kSparseTiles;
-    const int64_t blocks = (d + span - 1) / span;
-    if (!grid_fits(blocks, kBlock)) return GQ_ERR_INVALID_ARG;
+    const int64_t blocks = (d + kSparseSpan - 1) / kSparseSpan;
+    if (!grid_fits(blocks, kSparseBlock)) return GQ_ERR_INVALID_ARG;
     const dim3 grid((unsigned)blocks);
     int kpad = 1;
     while (kpad < K) kpad <<= 1;
-    const int lanes = kBlock / kpad;                            // threads per worker: 256 for K = 1 ... 4 for K = 64
-    if (p->scheme == GQ_LINEAR) hipLaunchKernelGGL(sparse_tile_kernel<0>, grid, dim3(kBlock), 0, s, S, K, lanes, d, (int *)agg_out);
-    else hipLaunchKernelGGL(sparse_tile_kernel<1>, grid, dim3(kBlock), 0, s, S, K, lanes, d, (int *)agg_out);
+    const int lanes = kSparseBlock / kpad;                      // threads per worker: 512 for K = 1 ... 8 for K = 64
+    if (p->scheme == GQ_LINEAR) hipLaunchKernelGGL(sparse_span_kernel<0>, grid, dim3(kSparseBlock), 0, s, S, K, lanes, d, (int *)agg_out);
+    else hipLaunchKernelGGL(sparse_span_kernel<1>, grid, dim3(kSparseBlock), 0, s, S, K, lanes, d, (int *)agg_out);
     if (launched() != GQ_OK) return GQ_ERR_DEVICE;
     return GQ_OK;
 }

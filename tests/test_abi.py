@@ -181,12 +181,16 @@ def test_argument_checks_need_no_device(gq):
     # sparse branch
     assert gq.compact_workspace_bytes(-1) == 0 and gq.compact_workspace_bytes(1 << 33) == 0
     assert gq.compact_workspace_bytes(0) == 16 and gq.compact_workspace_bytes(32768) == 32 and gq.compact_workspace_bytes(32769) == 40
-    cp = lambda p, lv=fake, d=64, cap=16, cnt=fake, ws=fake, wsb=1024: lib.gq_compact(lv, d, C.byref(p), fake, fake, cap, cnt, ws, wsb, None)
+    assert gq.tile_starts_len(0) == 1 and gq.tile_starts_len(4096) == 2 and gq.tile_starts_len(4097) == 3
+    assert gq.tile_starts_len(-1) == 0 and gq.tile_starts_len(1 << 33) == 0 and gq.tile_starts_len((1 << 32) - 1) == (1 << 20) + 1
+    cp = lambda p, lv=fake, d=64, cap=16, cnt=fake, ws=fake, wsb=1024, ts=None: lib.gq_compact(lv, d, C.byref(p), fake, fake, cap, cnt, ts, ws, wsb, None)
     assert cp(av) == gq.GQ_ERR_UNSUPPORTED and cp(ok, lv=odd) == I and cp(ok, d=-1) == I and cp(ok, d=1 << 33) == I
+    assert cp(ok, ts=C.c_void_p(0x1002)) == I
     assert cp(ok, cap=-1) == I and cp(ok, cnt=None) == I and cp(ok, cnt=odd) == I
     assert cp(ok, ws=None) == gq.GQ_ERR_WORKSPACE and cp(ok, d=1 << 20, wsb=8) == gq.GQ_ERR_WORKSPACE
     caps = (C.c_int64 * 2)(4, 4)
-    sa = lambda p, K=2, idx=arr, d=64, agg=fake: lib.gq_sparse_aggregate(idx, arr, arr, caps, K, d, C.byref(p), agg, None)
+    sa = lambda p, K=2, idx=arr, d=64, agg=fake, ts=None: lib.gq_sparse_aggregate(idx, arr, arr, caps, ts, K, d, C.byref(p), agg, None)
+    assert sa(ok, ts=(C.c_void_p * 2)(0x1000, 0x2002)) == I
     assert sa(P(gq.GQ_LINEAR, 127, agg=gq.GQ_AGG_I16)) == gq.GQ_ERR_UNSUPPORTED
     assert sa(ok, K=0) == I and sa(ok, idx=None) == I and sa(ok, agg=odd) == I and sa(ok, d=1 << 33) == I
     assert sa(ok, idx=(C.c_void_p * 2)(0x1000, 0x2002)) == I

@@ -720,12 +720,19 @@ def test_compact_matches_oracle(d, density):
     idx = torch.full((cap,), -1, dtype=torch.int32, device=DEV)
     val = torch.full((cap,), 0x5A, dtype=torch.int8, device=DEV)
     cnt = torch.full((1,), -1, dtype=torch.int64, device=DEV)
-    gq.compact(lv, d, params, idx, val, cnt)
+    nts = gq.tile_starts_len(d)
+    starts = torch.full((nts + 4,), -1, dtype=torch.int32, device=DEV)
+    gq.compact(lv, d, params, idx, val, cnt, tile_starts_out=starts)
     torch.cuda.synchronize()
     assert int(cnt.item()) == n
     gi, gv = host(idx).view(np.uint32), host(val)
     assert np.array_equal(gi[:n], widx) and np.array_equal(gv[:n].astype(np.int32), wval)
     assert np.all(gi[n:] == 0xFFFFFFFF) and np.all(gv[n:] == 0x5A)          # nothing written past the count
+    # the table of tile starts: entry t = how many of the oracle's indices lie below 4096 t; the last entry is the count
+    gs = host(starts).view(np.uint32)
+    assert nts == (d + 4095) // 4096 + 1
+    assert np.array_equal(gs[:nts], np.searchsorted(widx.astype(np.int64), 4096 * np.arange(nts, dtype=np.int64)).astype(np.uint32))
+    assert gs[nts - 1] == n and np.all(gs[nts:] == 0xFFFFFFFF)
     if n > 3:                                                                # a short buffer: true count, first entries
         idx2 = torch.full((3 + 4,), -1, dtype=torch.int32, device=DEV)[:3]
         val2 = torch.full((3 + 4,), 0x5A, dtype=torch.int8, device=DEV)[:3]
@@ -784,6 +791,29 @@ def test_sparse_path_equals_dense_aggregate(scheme, s, kind, K, d):
     assert torch.equal(agg[:d], dense) and bool((agg[d:] == 0x5A5A).all())
     want = O.quantize_aggregate(xh, nf, SCHEMES[scheme], s, 4242, 0)
     assert np.array_equal(host(agg)[:d].astype(np.int64), want)
+    # the same with the senders' tables of tile starts (no searches), and with a table for some workers only
+    tabs = []
+    for i in range(K):
+        t = torch.zeros(gq.tile_starts_len(d), dtype=torch.int32, device=DEV)
+        gq.compact(lvs[i], d, p, idxs[i], vals[i], cnts[i], tile_starts_out=t)
+        tabs.append(t)
+    for given in (tabs, [t if i % 2 == 0 else None for i, t in enumerate(tabs)]):
+        agg2 = torch.full((d + 8,), 0x5A5A, dtype=torch.int32, device=DEV)
+        gq.sparse_aggregate(idxs, vals, cnts, d, p, agg2, tile_starts=given)
+        torch.cuda.synchronize()
+        assert torch.equal(agg2, agg)
+    # lists cut short by their capacity: what was written is summed, with or without the table
+    if K > 1 and total > 8 * K:
+        short = [idx[:max(int(c.item()) // 2, 1)] for idx, c in zip(idxs, cnts)]
+        short_v = [v[:s_.numel()] for v, s_ in zip(vals, short)]
+        a1 = torch.zeros(d, dtype=torch.int32, device=DEV); a2 = torch.zeros(d, dtype=torch.int32, device=DEV)
+        gq.sparse_aggregate(short, short_v, cnts, d, p, a1)
+        gq.sparse_aggregate(short, short_v, cnts, d, p, a2, tile_starts=tabs)
+        torch.cuda.synchronize()
+        wi = [host(s_).view(np.uint32) for s_ in short]
+        wv = [host(v).astype(np.int32) for v in short_v]
+        assert np.array_equal(host(a1).astype(np.int64), O.sparse_aggregate(wi, wv, d, SCHEMES[scheme]))
+        assert torch.equal(a1, a2)
     if kind == "l2" and scheme == "linear" and K * d > 10000:
         # the sparse regime the paper's Theorem 1 speaks of: far fewer non-zeros than coordinates,
         # within the bound that follows from Eq. (2), s^2 + s*sqrt(nd)

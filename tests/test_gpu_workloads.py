@@ -214,7 +214,7 @@ def list_window(idx, lo, hi):
     return a, b
 
 
-def compact_with_guard(lv, d, p, ws):
+def compact_with_guard(lv, d, p, ws, starts=None):
     """gq_compact into buffers sized by a first counting call, with 8 guard entries behind them."""
     cnt = torch.zeros(1, dtype=torch.int64, device=DEV)
     probe_i = torch.empty(1, dtype=torch.int32, device=DEV)
@@ -225,7 +225,7 @@ def compact_with_guard(lv, d, p, ws):
     idx = torch.full((n + 8,), -1, dtype=torch.int32, device=DEV)
     val = torch.full((n + 8,), 0x5A, dtype=torch.int8, device=DEV)
     cnt.fill_(-1)
-    gq.compact(lv, d, p, idx, val, cnt, ws)
+    gq.compact(lv, d, p, idx, val, cnt, ws, tile_starts_out=starts)
     torch.cuda.synchronize()
     assert int(cnt.item()) == n
     assert bool((idx[n:] == -1).all()) and bool((val[n:] == 0x5A).all())       # nothing written past the count
@@ -252,10 +252,15 @@ def test_workload_c3_sparse_branch_at_full_size(kind):
     assert gq.compact_workspace_bytes(d) == 8 * (2 + 3357 + 53)
     idxs, vals, cnts, total = [], [], [], 0
     windows = spans(d, 33, edges=[1024 * 16384 * r for r in range(1, 7)])
+    tabs = []
+    edges = torch.arange(gq.tile_starts_len(d), dtype=torch.int64, device=DEV) * 4096
     for i in range(K):
-        n, idx, val, cnt = compact_with_guard(lvs[i], d, p, ws)
-        idxs.append(idx[:n]); vals.append(val[:n]); cnts.append(cnt); total += n
+        tab = torch.full((gq.tile_starts_len(d),), -1, dtype=torch.int32, device=DEV)
+        n, idx, val, cnt = compact_with_guard(lvs[i], d, p, ws, tab)
+        idxs.append(idx[:n]); vals.append(val[:n]); cnts.append(cnt); tabs.append(tab); total += n
         assert n == int(torch.count_nonzero(lvs[i]))
+        # the table of tile starts is the position of every multiple of 4096 in the (oracle-checked) index list
+        assert torch.equal(tab.to(torch.int64) & 0xFFFFFFFF, torch.searchsorted(idx[:n].to(torch.int64) & 0xFFFFFFFF, edges))
         if i in (0, K - 1):
             # the sender in full against the oracle: its own codes from the same gradient, its own list
             q = O.quantize(host(xs[i]), nf, O.LINEAR, s, SI.QUANT_SEED, i, 0)
@@ -284,6 +289,11 @@ def test_workload_c3_sparse_branch_at_full_size(kind):
     gq.sparse_aggregate(idxs, vals, cnts, d, p, agg)
     torch.cuda.synchronize()
     assert torch.equal(agg[:d], dense) and bool((agg[d:] == 0x5A5A).all())
+    agg_t = torch.full((d + 8,), 0x5A5A, dtype=torch.int32, device=DEV)
+    gq.sparse_aggregate(idxs, vals, cnts, d, p, agg_t, tile_starts=tabs)           # with the senders' tables: no searches
+    torch.cuda.synchronize()
+    assert torch.equal(agg_t, agg)
+    del agg_t
     for lo, hi in windows:
         want = O.quantize_aggregate([host(x[lo:hi]) for x in xs], nf, O.LINEAR, s, SI.QUANT_SEED, lo)
         assert np.array_equal(host(agg[lo:hi]).astype(np.int64), want), lo
@@ -321,11 +331,13 @@ def test_sparse_branch_with_32_bit_indices_up_to_the_limit():
         val = rng.integers(1, 128, pos.shape[0]).astype(np.int8) * rng.choice(np.array([-1, 1], np.int8), pos.shape[0])
         lv = torch.zeros(d, dtype=torch.int8, device=DEV)
         lv[torch.from_numpy(pos).to(DEV)] = torch.from_numpy(val).to(DEV)
-        n, idx, vv, cnt = compact_with_guard(lv, d, p, ws)
+        tab = torch.full((gq.tile_starts_len(d),), -1, dtype=torch.int32, device=DEV)
+        n, idx, vv, cnt = compact_with_guard(lv, d, p, ws, tab)
         assert n == pos.shape[0]
+        assert np.array_equal(host(tab).view(np.uint32).astype(np.int64), np.searchsorted(pos, 4096 * np.arange(gq.tile_starts_len(d), dtype=np.int64)))
         assert np.array_equal(host(idx[:n]).view(np.uint32).astype(np.int64), pos)
         assert np.array_equal(host(vv[:n]), val)
-        lvs.append(lv); lists.append((idx[:n], vv[:n], cnt)); pos_all.append(pos); val_all.append(val)
+        lvs.append(lv); lists.append((idx[:n], vv[:n], cnt, tab)); pos_all.append(pos); val_all.append(val)
         # the oracle's compaction on windows of the same vector
         for lo, hi in [(0, 1 << 20), (half - (1 << 19), half + (1 << 19)), (d - (1 << 20), d),
                        (255 * 16384 * 1024 - 4096, 255 * 16384 * 1024 + 4096)]:
@@ -346,6 +358,11 @@ def test_sparse_branch_with_32_bit_indices_up_to_the_limit():
     # construction (scatter-add of the positions), and against the oracle's receiver on windows
     agg = torch.empty(d, dtype=torch.int32, device=DEV)
     gq.sparse_aggregate([l[0] for l in lists], [l[1] for l in lists], [l[2] for l in lists], d, p, agg)
+    agg_t = torch.empty(d, dtype=torch.int32, device=DEV)
+    gq.sparse_aggregate([l[0] for l in lists], [l[1] for l in lists], [l[2] for l in lists], d, p, agg_t, tile_starts=[l[3] for l in lists])
+    torch.cuda.synchronize()
+    assert torch.equal(agg_t, agg)
+    del agg_t
     dense = torch.empty(d, dtype=torch.int32, device=DEV)
     gq.int_aggregate([lv.view(torch.uint8) for lv in lvs], None, d, p, dense)
     torch.cuda.synchronize()
