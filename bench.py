@@ -51,6 +51,8 @@ def parse():
                     help="with --per-bucket-norm: the headline ms_per_step is the two-stream schedule (default: serial)")
     ap.add_argument("--no-window-ab", action="store_true",
                     help="skip the interleaved timing of the fused call with its write windows forced off and on")
+    ap.add_argument("--norm", default=None, choices=["linf", "l2"],
+                    help="override the workload's norm (c3 under the L2 norm is the low-density case of the sparse branch)")
     ap.add_argument("--windows", default="default", choices=["default", "on", "off"],
                     help="write windows of the fused call in the timed steps: the library's policy, forced on, or forced off "
                          "(gq_params.flags); for profiling one variant at a time")
@@ -214,6 +216,8 @@ def main():
     cfg = SI.CONFIGS[args.workload]
     K, d, s = cfg["K"], cfg["d"], cfg["s"]
     scheme = gq.GQ_LINEAR if cfg["scheme"] == "linear" else gq.GQ_EXP
+    if args.norm:
+        cfg = dict(cfg, norm=args.norm)
     kind = {"linf": gq.GQ_NORM_LINF, "l2": gq.GQ_NORM_L2}[cfg["norm"]]
     win_flags = {"default": 0, "on": gq.GQ_FLAG_WRITE_WINDOWS_ON, "off": gq.GQ_FLAG_WRITE_WINDOWS_OFF}[args.windows]
     params = gq.make_params(scheme, s, gq.GQ_PACK_I8, gq.GQ_AGG_I32, seed=SI.QUANT_SEED, flags=win_flags)
