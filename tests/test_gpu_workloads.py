@@ -558,3 +558,45 @@ def test_workload_c5_per_bucket_norms_two_streams_equal_the_serial_schedule():
     gq.bucketed_quantize_aggregate(small, bucket, gq.GQ_NORM_LINF, p, norms, None, None, o2, side_stream=side)
     torch.cuda.synchronize()
     assert torch.equal(o1, o2) and float(norms.item()) == max(float(x.abs().max()) for x in small)
+
+
+def test_per_bucket_schedule_replays_from_a_hip_graph():
+    # the two-stream schedule forks and joins its side stream with events inside the call, so the whole call can be
+    # captured from the main stream and replayed; every replay is compared with the eager serial schedule on fresh data
+    K, d, bucket, s = 8, 5 * (1 << 20) + 4099, 1 << 20, 15
+    g0 = torch.Generator(device="cpu").manual_seed(77)
+    xs = [(torch.randn(d, generator=g0) * 1e-3).to(DEV) for _ in range(K)]
+    nb = SI.num_buckets(d, bucket)
+    p = gq.make_params(gq.GQ_LINEAR, s, gq.GQ_PACK_I8, gq.GQ_AGG_I32, seed=SI.QUANT_SEED)
+    ws = torch.empty(gq.bucketed_workspace_bytes(K, d, bucket), dtype=torch.uint8, device=DEV)
+    norms = torch.zeros(nb, device=DEV)
+    flags = torch.zeros(nb, dtype=torch.int32, device=DEV)
+    agg = torch.zeros(d, dtype=torch.int32, device=DEV)
+    out = torch.zeros(d, device=DEV)
+    side = torch.cuda.Stream()
+
+    def two_streams():
+        gq.bucketed_quantize_aggregate(xs, bucket, gq.GQ_NORM_L2, p, norms, flags, agg, out, ws, side_stream=side)
+
+    two_streams()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    cap = torch.cuda.Stream()
+    cap.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(cap):
+        with torch.cuda.graph(graph, stream=cap):
+            two_streams()
+    torch.cuda.current_stream().wait_stream(cap)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for x in xs:
+            x.copy_((torch.randn(d, generator=g0) * (1e-3 * (rep + 1))).to(DEV))
+        norms.fill_(-1.0); agg.fill_(-1); out.fill_(-1.0); flags.fill_(9)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (norms.clone(), agg.clone(), out.clone(), flags.clone())
+        norms.fill_(-2.0); agg.fill_(-2); out.fill_(-2.0); flags.fill_(8)
+        gq.bucketed_quantize_aggregate(xs, bucket, gq.GQ_NORM_L2, p, norms, flags, agg, out, ws)       # eager, serial
+        torch.cuda.synchronize()
+        assert torch.equal(got[0], norms) and torch.equal(got[1], agg) and torch.equal(got[2], out) and torch.equal(got[3], flags)
+        assert float(norms.min()) > 0 and int(agg.abs().max()) > 0 and int(flags.max()) == 0
