@@ -12,9 +12,9 @@ namespace gq {
 
 // =============================================================================================
 // Algorithm 1's sparse branch.  Sender side: the (index, code) pairs of a worker's non-zero int8 codes in
-// increasing index order, in one pass over the codes (a chained scan over the blocks gives every block its
-// place in the list; the non-zeros inside a block are ranked with wave scans).  Receiver side: the K sorted
-// lists are merged tile by tile into the dense int32 sum.
+// increasing index order, in one pass over the codes (every workgroup learns its place in the list from the
+// counts the workgroups before it publish; the non-zeros inside a workgroup's span are ranked with wave scans).
+// Receiver side: the K sorted lists are added span by span into the dense int32 sum.
 // =============================================================================================
 constexpr int kCompactBlock = 256;
 constexpr int kCompactTile = kCompactBlock * 16;        // codes per tile: one 128-bit load per thread
@@ -40,30 +40,6 @@ __device__ __forceinline__ uint32_t count_unit(const u32x4 &c)
 {
     return (uint32_t)(__builtin_popcount(nonzero_bytes(c.x)) + __builtin_popcount(nonzero_bytes(c.y)) +
                       __builtin_popcount(nonzero_bytes(c.z)) + __builtin_popcount(nonzero_bytes(c.w)));
-}
-
-// Exclusive prefix sum of one value per thread over the block; every thread must call it.
-// `total` receives the block's sum.  sh must hold BLOCK/64 words.
-template <int BLOCK>
-__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *sh, uint32_t *total)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    uint32_t incl = v;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t t = (uint32_t)__shfl_up((int)incl, off, 64);
-        if (lane >= off) incl += t;
-    }
-    if (lane == 63) sh[wave] = incl;
-    __syncthreads();
-    uint32_t base = 0, sum = 0;
-    for (int i = 0; i < BLOCK / 64; i++) {
-        if (i < wave) base += sh[i];
-        sum += sh[i];
-    }
-    __syncthreads();
-    *total = sum;
-    return base + incl - v;
 }
 
 // ---------------------------------------------------------------------------------------------------------
