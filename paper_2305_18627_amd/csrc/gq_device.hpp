@@ -3,6 +3,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace gq {
 
@@ -12,6 +13,16 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef short i16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBlock = 256;          // threads per workgroup: four wave64
+
+// f(integral_constant<int, BEGIN>), ..., f(integral_constant<int, END - 1>): a loop whose index is a compile-time
+// constant in the body, so that it is unrolled by the language and not at the optimizer's discretion.
+template <int BEGIN, int END, typename F> __device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (BEGIN < END) {
+        f(std::integral_constant<int, BEGIN>{});
+        static_for<BEGIN + 1, END>(f);
+    }
+}
 constexpr int kMaxWorkers = 64;
 
 // Per-worker device pointers, passed to the kernels by value.

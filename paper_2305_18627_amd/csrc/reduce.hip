@@ -145,40 +145,41 @@ exp_reduce_kernel(LevelCPtrs Lv, int K, int64_t d, int s, uint64_t seed, uint64_
     // the Philox words of the node groups in use, one slot per tree level; the binary32 path keeps them complemented
     uint32_t grp[L + 1][4];
     constexpr int kBatch = NPAD < 8 ? NPAD : 8;
-#pragma unroll
-    for (int w0 = 0; w0 < NPAD; w0 += kBatch) {
+    static_for<0, NPAD / kBatch>([&](auto batch) {
+        constexpr int w0 = decltype(batch)::value * kBatch;
         uint32_t words[kBatch];
 #pragma unroll
         for (int j = 0; j < kBatch; j++) words[j] = fetch(w0 + j);
-#pragma unroll
-        for (int j = 0; j < kBatch; j++) {
-            const int i = w0 + j;                            // leaf index; the stack depth is popcount(i)
-            int top = __builtin_popcount((unsigned)i);
+        static_for<0, kBatch>([&](auto jj) {
+            constexpr int j = decltype(jj)::value;
+            constexpr int i = w0 + j;                        // leaf index; the stack depth is popcount(i)
+            constexpr int top0 = __builtin_popcount((unsigned)i);
 #pragma unroll
             for (int c = 0; c < 4; c++) {
-                if (kFloat) {
-                    st_f[top][c] = leaf_value[(words[j] >> (8 * c)) & 255u];
+                if constexpr (kFloat) {
+                    st_f[top0][c] = leaf_value[(words[j] >> (8 * c)) & 255u];
                 } else {
                     // code k >= 1 of the exponential grid -> e = s - k + 1 + L; code 0 is zero
                     const int q = (int)(int8_t)(words[j] >> (8 * c));
-                    st_sg[top][c] = q;
-                    st_e[top][c] = q ? s + 1 + L - abs(q) : kZeroE;
+                    st_sg[top0][c] = q;
+                    st_e[top0][c] = q ? s + 1 + L - abs(q) : kZeroE;
                 }
             }
-#pragma unroll
-            for (int lvl = 1; lvl <= L; lvl++) {
-                if (((i + 1) & ((1 << lvl) - 1)) == 0) {     // a subtree of 2^lvl leaves is complete
-                    const int node = (NPAD >> lvl) + (i >> lvl);            // heap numbering
+            static_for<1, L + 1>([&](auto ll) {
+                constexpr int lvl = decltype(ll)::value;
+                if constexpr (((i + 1) & ((1 << lvl) - 1)) == 0) {       // a subtree of 2^lvl leaves is complete
+                    constexpr int top = top0 - (lvl - 1);                // one partial result was folded per level below
+                    constexpr int node = (NPAD >> lvl) + (i >> lvl);     // heap numbering
                     // the root shares its group with nodes 2 and 3 (one level down) when a call serves four nodes
-                    const int slot = (PER == 4 && node == 1 && NPAD >= 4) ? lvl - 1 : lvl;
-                    if (first_of_group<NPAD, PER>(node)) {
+                    constexpr int slot = (PER == 4 && node == 1 && NPAD >= 4) ? lvl - 1 : lvl;
+                    if constexpr (first_of_group<NPAD, PER>(node)) {
                         const Words4 r = philox4x32_10(c_lo, c_hi, (uint32_t)(node / PER), 1u, k0, k1);
 #pragma unroll
                         for (int c = 0; c < 4; c++) grp[slot][c] = kFloat ? ~r.w[c] : r.w[c];
                     }
 #pragma unroll
                     for (int c = 0; c < 4; c++) {
-                        if (kFloat) {
+                        if constexpr (kFloat) {
                             // the top s bits of the node's complemented field, moved to the top of the mantissa
                             const uint32_t A = __builtin_amdgcn_ubfe(grp[slot][c], (uint32_t)(W * (node % PER) + W - s), (uint32_t)s)
                                                << (23 - s);
@@ -189,11 +190,10 @@ exp_reduce_kernel(LevelCPtrs Lv, int K, int64_t d, int s, uint64_t seed, uint64_
                             st_sg[top - 1][c] = o.sg; st_e[top - 1][c] = o.e;
                         }
                     }
-                    top--;
                 }
-            }
-        }
-    }
+            });
+        });
+    });
     int root[4];                                            // sign * e of the root, 0 for zero
 #pragma unroll
     for (int c = 0; c < 4; c++) {
@@ -281,39 +281,39 @@ exp_reduce_f16_kernel(LevelCPtrs Lv, int K, int64_t d, int s, uint64_t seed, uin
     f16x2 st[L + 1][2];                                      // the stack: coordinates (0,1) and (2,3) of every partial result
     uint32_t grp[L + 1][4];                                  // masked complemented Philox words of the node groups in use
     constexpr int kBatch = NPAD < 8 ? NPAD : 8;
-#pragma unroll
-    for (int w0 = 0; w0 < NPAD; w0 += kBatch) {
+    static_for<0, NPAD / kBatch>([&](auto batch) {
+        constexpr int w0 = decltype(batch)::value * kBatch;
         uint32_t words[kBatch];
 #pragma unroll
         for (int j = 0; j < kBatch; j++) words[j] = fetch(w0 + j);
-#pragma unroll
-        for (int j = 0; j < kBatch; j++) {
-            const int i = w0 + j;                            // leaf index; the stack depth is popcount(i)
-            int top = __builtin_popcount((unsigned)i);
-            st[top][0] = (f16x2){leaf_value[words[j] & 255u], leaf_value[(words[j] >> 8) & 255u]};
-            st[top][1] = (f16x2){leaf_value[(words[j] >> 16) & 255u], leaf_value[words[j] >> 24]};
-#pragma unroll
-            for (int lvl = 1; lvl <= L; lvl++) {
-                if (((i + 1) & ((1 << lvl) - 1)) == 0) {     // a subtree of 2^lvl leaves is complete
-                    const int node = (NPAD >> lvl) + (i >> lvl);            // heap numbering
-                    const int slot = (node == 1 && NPAD >= 4) ? lvl - 1 : lvl;   // the root shares its group with nodes 2 and 3
-                    if (first_of_group<NPAD, PER>(node)) {
+        static_for<0, kBatch>([&](auto jj) {
+            constexpr int j = decltype(jj)::value;
+            constexpr int i = w0 + j;                        // leaf index; the stack depth is popcount(i)
+            constexpr int top0 = __builtin_popcount((unsigned)i);
+            st[top0][0] = (f16x2){leaf_value[words[j] & 255u], leaf_value[(words[j] >> 8) & 255u]};
+            st[top0][1] = (f16x2){leaf_value[(words[j] >> 16) & 255u], leaf_value[words[j] >> 24]};
+            static_for<1, L + 1>([&](auto ll) {
+                constexpr int lvl = decltype(ll)::value;
+                if constexpr (((i + 1) & ((1 << lvl) - 1)) == 0) {       // a subtree of 2^lvl leaves is complete
+                    constexpr int top = top0 - (lvl - 1);                // one partial result was folded per level below
+                    constexpr int node = (NPAD >> lvl) + (i >> lvl);     // heap numbering
+                    constexpr int slot = (node == 1 && NPAD >= 4) ? lvl - 1 : lvl;   // the root shares its group with nodes 2 and 3
+                    if constexpr (first_of_group<NPAD, PER>(node)) {
                         const Words4 r = philox4x32_10(c_lo, c_hi, (uint32_t)(node / PER), 1u, k0, k1);
 #pragma unroll
                         for (int c = 0; c < 4; c++) grp[slot][c] = ~r.w[c] & keep;
                     }
                     // byte `node % 4` of the words of coordinates (0,1) resp. (2,3) into the low bytes of the two halves
                     constexpr uint32_t kZero = 0x0Cu;        // v_perm_b32 selector of a zero byte
-                    const uint32_t sel = (kZero << 24) | ((uint32_t)(4 + node % PER) << 16) | (kZero << 8) | (uint32_t)(node % PER);
+                    constexpr uint32_t sel = (kZero << 24) | ((uint32_t)(4 + node % PER) << 16) | (kZero << 8) | (uint32_t)(node % PER);
                     const uint32_t A01 = __builtin_amdgcn_perm(grp[slot][1], grp[slot][0], sel) << 2;
                     const uint32_t A23 = __builtin_amdgcn_perm(grp[slot][3], grp[slot][2], sel) << 2;
                     st[top - 1][0] = alg2_pair_f16x2(st[top - 1][0], st[top][0], A01);
                     st[top - 1][1] = alg2_pair_f16x2(st[top - 1][1], st[top][1], A23);
-                    top--;
                 }
-            }
-        }
-    }
+            });
+        });
+    });
     int root[4];                                            // sign * e of the root, 0 for zero
 #pragma unroll
     for (int c = 0; c < 4; c++) {
