@@ -189,6 +189,14 @@ def time_rows(gq, torch, xs, norm, params, cfg, args):
         tot = float(sum(nnz))
         # the method's bytes: every code read once, every pair (4-byte index + 1-byte code) written once
         rows["compact_xK"] = timed(compact_all, 1.0 * K * d + 5.0 * tot)
+
+        # the sender in one call, straight from the gradients: 4 bytes read per coordinate, 5 written per non-zero
+        def quantize_compact_all():
+            for i in range(K):
+                gq.quantize_compact(xs[i], norm, p, i, 0, idxs[i], vals[i], cnts[i], ws, tile_starts_out=tabs[i])
+
+        rows["quantize_compact_xK"] = timed(quantize_compact_all, 4.0 * K * d + 5.0 * tot)
+        rows["quantize_compact_xK"]["two_calls_ms"] = rows["quantize_xK"]["ms"] + rows["compact_xK"]["ms"]
         if aggf == gq.GQ_AGG_I32:
             # with the senders' tables of tile starts, and without them (the receiver then searches the lists)
             rows["sparse_aggregate"] = timed(lambda: gq.sparse_aggregate(idxs, vals, cnts, d, p, agg, tile_starts=tabs), 4.0 * d + 5.0 * tot)

@@ -270,6 +270,17 @@ gq_status gq_compact(const void *levels, int64_t d, const gq_params *p /* host *
                      int8_t *values_out, int64_t capacity, uint64_t *count_out, uint32_t *tile_starts_out,
                      void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* The sender side in one call (Algorithm 1: the quantisation loop followed by the sparse branch's selection of
+ * the non-zero codes): what gq_quantize (int8 codes) followed by gq_compact writes -- the same list, count and tile
+ * starts, bit for bit, from the same rounding rule and random stream -- without the dense codes ever reaching
+ * memory: 4 d bytes read, 5 bytes per non-zero written.
+ *   x, norm, worker, index_base   as for gq_quantize (p->pack must be GQ_PACK_I8; both settings of p->rng_bits)
+ *   the other arguments           as for gq_compact; indices count from x[0]; d <= 2^32 - 1 */
+gq_status gq_quantize_compact(const float *x, int64_t d, const float *norm, const gq_params *p /* host */,
+                              uint32_t worker, int64_t index_base, uint32_t *indices_out, int8_t *values_out,
+                              int64_t capacity, uint64_t *count_out, uint32_t *tile_starts_out,
+                              void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Receiver side of the sparse branch: the dense integer sum A_j of the K workers' lists, equal to what
  * gq_int_aggregate forms from the dense codes.
  *   indices, values  host arrays of K device lists as written by gq_compact (indices strictly increasing)

@@ -24,6 +24,7 @@ GQ_FLAG_WRITE_WINDOWS_OFF, GQ_FLAG_WRITE_WINDOWS_ON = 1, 2
 EXPORTS = ("gq_version", "gq_status_string", "gq_check_width", "gq_norm_workspace_bytes", "gq_global_norm",
            "gq_global_norm_static", "gq_bucketed_workspace_bytes", "gq_bucketed_quantize_aggregate",
            "gq_quantize", "gq_int_aggregate", "gq_dequantize", "gq_fused_quantize_aggregate", "gq_exp_reduce", "gq_avg_reduce", "gq_compact_workspace_bytes", "gq_tile_starts_len", "gq_compact",
+           "gq_quantize_compact",
            "gq_sparse_aggregate")
 
 
@@ -63,6 +64,7 @@ def _load():
         "gq_compact_workspace_bytes": (sz, [i64]),
         "gq_tile_starts_len": (i64, [i64]),
         "gq_compact": (i32, [vp, i64, pp, vp, vp, i64, vp, vp, vp, sz, vp]),
+        "gq_quantize_compact": (i32, [vp, i64, vp, pp, u32, i64, vp, vp, i64, vp, vp, vp, sz, vp]),
         "gq_sparse_aggregate": (i32, [C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(i64), C.POINTER(vp), i32, i64, pp, vp, vp]),
         "gq_fused_quantize_aggregate": (i32, [C.POINTER(vp), i32, i64, vp, pp, i64, vp, vp, C.POINTER(vp),
                                                C.POINTER(vp), vp]),
@@ -283,6 +285,23 @@ def compact(levels, d, params, indices_out, values_out, count_out, workspace=Non
                          indices_out.numel(), _ptr(count_out), _ptr(tile_starts_out), _ptr(workspace),
                          workspace.numel() * workspace.element_size(), _stream(stream))
     _check(st, "gq_compact")
+    return workspace
+
+
+def quantize_compact(x, norm, params, worker, index_base, indices_out, values_out, count_out, workspace=None, stream=None,
+                     tile_starts_out=None):
+    """gq_quantize_compact: the list gq_quantize + gq_compact would write, straight from the gradient.  Returns the
+    workspace used."""
+    d = _need_grads([x])
+    _need(norm, 4, "norm"); _need(count_out, 8, "count_out")
+    _need(values_out, indices_out.numel(), "values_out"); _need(indices_out, 0, "indices_out")
+    _need(tile_starts_out, 4 * tile_starts_len(d), "tile_starts_out")
+    if workspace is None:
+        workspace = torch.empty(compact_workspace_bytes(d), dtype=torch.uint8, device=count_out.device)
+    st = _lib.gq_quantize_compact(_ptr(x), d, _ptr(norm), C.byref(params), int(worker), int(index_base), _ptr(indices_out),
+                                  _ptr(values_out), indices_out.numel(), _ptr(count_out), _ptr(tile_starts_out), _ptr(workspace),
+                                  workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(st, "gq_quantize_compact")
     return workspace
 
 

@@ -154,6 +154,31 @@ template <> struct Round<1> {
     }
 };
 
+// Four consecutive coordinates of a gradient (vector v); nvalid < 4 of them exist at the ragged end, zeros beyond.
+__device__ __forceinline__ f32x4 load_coords(const float *x, int64_t v, int nvalid)
+{
+    if (nvalid == 4) return __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(x) + v);
+    f32x4 a = {0.0f, 0.0f, 0.0f, 0.0f};
+    const float *t = x + (v << 2);
+    if (nvalid > 0) a.x = t[0];
+    if (nvalid > 1) a.y = t[1];
+    if (nvalid > 2) a.z = t[2];
+    return a;
+}
+
+// Four int8 codes as one word, coordinate i in byte i.
+__device__ __forceinline__ uint32_t pack_bytes(const int *q)
+{
+    return (uint32_t)(q[0] & 255) | ((uint32_t)(q[1] & 255) << 8) | ((uint32_t)(q[2] & 255) << 16) | ((uint32_t)(q[3] & 255) << 24);
+}
+
+// Short draws: coordinate j of a vector takes the low (j even) or high (j odd) half of word j / 2 of the vector's pair
+// of Philox words, moved to the top of a 32-bit word with zeros below.
+__device__ __forceinline__ uint32_t short_draw(const uint32_t *pair, int j)
+{
+    return (j & 1) ? (pair[j >> 1] & 0xFFFF0000u) : (pair[j >> 1] << 16);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Wave reductions for the norm: DPP inside a row of 16 lanes (quad permutes, then the two mirror
 // patterns), ds_swizzle across the two rows of a half wave, readlane across the halves.

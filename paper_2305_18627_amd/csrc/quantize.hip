@@ -29,17 +29,6 @@ namespace gq {
 //               windows (see below)
 //   HALF        short draws: 16 random bits per coordinate, one Philox call per eight coordinates
 // =============================================================================================
-__device__ __forceinline__ f32x4 load_coords(const float *x, int64_t v, int nvalid)
-{
-    if (nvalid == 4) return __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(x) + v);
-    f32x4 a = {0.0f, 0.0f, 0.0f, 0.0f};
-    const float *t = x + (v << 2);
-    if (nvalid > 0) a.x = t[0];
-    if (nvalid > 1) a.y = t[1];
-    if (nvalid > 2) a.z = t[2];
-    return a;
-}
-
 // OR over the 8 lanes that share one 32-bit sign word.  Every lane of the wave must be active.
 __device__ __forceinline__ uint32_t or_over_8_lanes(uint32_t v)
 {
@@ -59,10 +48,6 @@ __device__ __forceinline__ uint32_t sign_nibble(int *q)
         q[i] = abs(q[i]);
     }
     return nib;
-}
-__device__ __forceinline__ uint32_t pack_bytes(const int *q)
-{
-    return (uint32_t)(q[0] & 255) | ((uint32_t)(q[1] & 255) << 8) | ((uint32_t)(q[2] & 255) << 16) | ((uint32_t)(q[3] & 255) << 24);
 }
 __device__ __forceinline__ uint32_t pack_nibbles(const int *q)
 {
@@ -153,10 +138,6 @@ __device__ __forceinline__ ShortDraws share_short_draws(const Words4 &r, bool od
     o.a[0] = odd ? got0 : r.w[0]; o.a[1] = odd ? got1 : r.w[1];
     o.b[0] = odd ? r.w[2] : got0; o.b[1] = odd ? r.w[3] : got1;
     return o;
-}
-__device__ __forceinline__ uint32_t short_draw(const uint32_t *pair, int j)
-{
-    return (j & 1) ? (pair[j >> 1] & 0xFFFF0000u) : (pair[j >> 1] << 16);
 }
 
 // The launch covers the vectors v0 <= v < vend of the buffers (HALF: v0 = 0).  With UNIFORM_HI the host

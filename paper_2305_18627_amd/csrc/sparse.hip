@@ -163,10 +163,11 @@ __device__ __forceinline__ void block_scan_tiles(const uint32_t *cnt, uint32_t *
     __syncthreads();
 }
 
-__global__ void __launch_bounds__(kCompactBlock)
-compact_onepass_kernel(const uint8_t *__restrict__ lv, int64_t d, uint64_t *__restrict__ state, int64_t nspans,
-                       uint32_t *__restrict__ indices_out, int8_t *__restrict__ values_out, int64_t capacity,
-                       uint64_t *__restrict__ count_out, uint32_t *__restrict__ tile_starts_out)
+// The list entries of one span, given its codes: c[j] holds the 16 codes of unit threadIdx.x of tile j of the span
+// (zeros past the end of the buffer).  Every thread of the workgroup must call it.
+__device__ __forceinline__ void emit_span(const u32x4 (&c)[kCompactTiles], int64_t d, uint64_t *__restrict__ state, int64_t nspans,
+                                          uint32_t *__restrict__ indices_out, int8_t *__restrict__ values_out, int64_t capacity,
+                                          uint64_t *__restrict__ count_out, uint32_t *__restrict__ tile_starts_out)
 {
     __shared__ uint32_t sh[(kCompactBlock / 64) * (kCompactTiles / 2)];
     __shared__ uint32_t s_idx[kCompactTile];
@@ -176,9 +177,6 @@ compact_onepass_kernel(const uint8_t *__restrict__ lv, int64_t d, uint64_t *__re
     uint64_t *group_words = span_words + nspans;
     const int64_t span = blockIdx.x;
     const int64_t t0 = span * (kCompactBlock * kCompactTiles) + threadIdx.x;
-    u32x4 c[kCompactTiles];
-#pragma unroll
-    for (int j = 0; j < kCompactTiles; j++) c[j] = load_code_unit(lv, t0 + (int64_t)j * kCompactBlock, d);
     uint32_t cnt[kCompactTiles], rank[kCompactTiles], total[kCompactTiles];
 #pragma unroll
     for (int j = 0; j < kCompactTiles; j++) cnt[j] = count_unit(c[j]);
@@ -269,6 +267,125 @@ compact_onepass_kernel(const uint8_t *__restrict__ lv, int64_t d, uint64_t *__re
         base += total[j];
         __syncthreads();                                     // the staging area is reused by the next tile
     }
+}
+
+
+__global__ void __launch_bounds__(kCompactBlock)
+compact_onepass_kernel(const uint8_t *__restrict__ lv, int64_t d, uint64_t *__restrict__ state, int64_t nspans,
+                       uint32_t *__restrict__ indices_out, int8_t *__restrict__ values_out, int64_t capacity,
+                       uint64_t *__restrict__ count_out, uint32_t *__restrict__ tile_starts_out)
+{
+    const int64_t t0 = (int64_t)blockIdx.x * (kCompactBlock * kCompactTiles) + threadIdx.x;
+    u32x4 c[kCompactTiles];
+#pragma unroll
+    for (int j = 0; j < kCompactTiles; j++) c[j] = load_code_unit(lv, t0 + (int64_t)j * kCompactBlock, d);
+    emit_span(c, d, state, nspans, indices_out, values_out, capacity, count_out, tile_starts_out);
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Sender side without the dense codes: Algorithm 1's quantisation loop for one worker feeding the list directly.
+// A workgroup quantises its span tile by tile (the same rounding, random stream and call indices as gq_quantize),
+// passes the code words of a tile through LDS so that every thread ends up with 16 consecutive codes, and hands the
+// span to emit_span: 4 d bytes read, 5 nnz written, and the codes never reach memory.
+//   full draws   a thread owns vectors t, t + 256, t + 512, t + 768 of a tile (a wave reads 1 KiB per load)
+//   short draws  a thread owns the vector pairs of calls t and t + 256 of a tile (one Philox call per eight coordinates)
+// The loads of the next tile are issued before the current tile is rounded.
+// ---------------------------------------------------------------------------------------------------------
+template <int SCHEME, bool UNIFORM_HI, bool HALF, bool WHOLE>
+__device__ __forceinline__ void quantize_span(const float *__restrict__ x, int64_t d, const Scale &sc, uint64_t seed, uint32_t worker,
+                                              uint64_t call_base, uint32_t (*stage)[kCompactTile / 4], u32x4 (&c)[kCompactTiles])
+{
+    constexpr int kTileVecs = kCompactTile / 4;
+    constexpr int kVecs = kTileVecs / kCompactBlock;                  // vectors per thread and tile: 4
+    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    const int64_t nfull = d >> 2;
+    const int64_t vspan = (int64_t)blockIdx.x * (kCompactSpan / 4);  // scalar
+    const int t = (int)threadIdx.x;
+    int li[kVecs];
+#pragma unroll
+    for (int i = 0; i < kVecs; i++) li[i] = HALF ? 2 * (t + kCompactBlock * (i >> 1)) + (i & 1) : i * kCompactBlock + t;
+    auto load_tile = [&](int j, f32x4 *g) {
+#pragma unroll
+        for (int i = 0; i < kVecs; i++) {
+            const int64_t v = vspan + (int64_t)j * kTileVecs + li[i];
+            if (WHOLE) g[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(x) + v);
+            else g[i] = load_coords(x, v, v < nfull ? 4 : (v == nfull ? (int)(d & 3) : 0));
+        }
+    };
+    f32x4 g[kVecs], gn[kVecs];
+    load_tile(0, g);
+    static_for<0, kCompactTiles>([&](auto jj) {
+        constexpr int j = decltype(jj)::value;
+        if constexpr (j + 1 < kCompactTiles) load_tile(j + 1, gn);
+        uint32_t *st = stage[j & 1];
+        const int64_t vt = vspan + (int64_t)j * kTileVecs;           // scalar
+        const uint64_t first = call_base + (uint64_t)(HALF ? (vt >> 1) : vt);
+        auto counter = [&](int local, uint32_t &c_lo, uint32_t &c_hi) {
+            if (UNIFORM_HI) {                                         // host: the launch stays below the next multiple of 2^32 calls
+                c_hi = (uint32_t)(first >> 32);
+                c_lo = (uint32_t)first + (uint32_t)local;
+            } else {
+                const uint64_t cc = first + (uint64_t)local;
+                c_lo = (uint32_t)cc;
+                c_hi = (uint32_t)(cc >> 32);
+            }
+        };
+        auto emit = [&](int i, const uint32_t *draw) {
+            const int q[4] = {Round<SCHEME>::code(g[i].x, sc, draw[0]), Round<SCHEME>::code(g[i].y, sc, draw[1]),
+                              Round<SCHEME>::code(g[i].z, sc, draw[2]), Round<SCHEME>::code(g[i].w, sc, draw[3])};
+            uint32_t w = pack_bytes(q);
+            if (!WHOLE) {                                             // no entries for coordinates past the end
+                const int64_t v = vt + li[i];
+                const int nv = v < nfull ? 4 : (v == nfull ? (int)(d & 3) : 0);
+                if (nv < 4) w &= (1u << (8 * nv)) - 1u;
+            }
+            st[li[i]] = w;
+        };
+        if (HALF) {
+#pragma unroll
+            for (int h = 0; h < kVecs / 2; h++) {
+                uint32_t c_lo, c_hi;
+                counter(t + kCompactBlock * h, c_lo, c_hi);
+                const Words4 r = philox4x32_10(c_lo, c_hi, worker, 0u, k0, k1);
+                uint32_t da[4], db[4];
+#pragma unroll
+                for (int i = 0; i < 4; i++) { da[i] = short_draw(&r.w[0], i); db[i] = short_draw(&r.w[2], i); }
+                emit(2 * h, da);
+                emit(2 * h + 1, db);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < kVecs; i++) {
+                uint32_t c_lo, c_hi;
+                counter(li[i], c_lo, c_hi);
+                const Words4 r = philox4x32_10(c_lo, c_hi, worker, 0u, k0, k1);
+                emit(i, r.w);
+            }
+        }
+        __syncthreads();
+        // two staging buffers in turn: the barrier of the next tile separates these reads from the writes of the tile after
+        c[j] = *reinterpret_cast<const u32x4 *>(&st[4 * t]);
+        if constexpr (j + 1 < kCompactTiles) {
+#pragma unroll
+            for (int i = 0; i < kVecs; i++) g[i] = gn[i];
+        }
+    });
+}
+
+template <int SCHEME, bool UNIFORM_HI, bool HALF>
+__global__ void __launch_bounds__(kCompactBlock)
+quantize_compact_kernel(const float *__restrict__ x, int64_t d, const float *__restrict__ norm, int s, uint64_t seed, uint32_t worker,
+                        uint64_t call_base, uint64_t *__restrict__ state, int64_t nspans, uint32_t *__restrict__ indices_out,
+                        int8_t *__restrict__ values_out, int64_t capacity, uint64_t *__restrict__ count_out,
+                        uint32_t *__restrict__ tile_starts_out)
+{
+    __shared__ __attribute__((aligned(16))) uint32_t stage[2][kCompactTile / 4];
+    const Scale sc = make_scale<SCHEME>(*norm, s);
+    const bool whole = ((int64_t)blockIdx.x + 1) * kCompactSpan <= (d & ~(int64_t)3);     // uniform over the workgroup
+    u32x4 c[kCompactTiles];
+    if (whole) quantize_span<SCHEME, UNIFORM_HI, HALF, true>(x, d, sc, seed, worker, call_base, stage, c);
+    else quantize_span<SCHEME, UNIFORM_HI, HALF, false>(x, d, sc, seed, worker, call_base, stage, c);
+    emit_span(c, d, state, nspans, indices_out, values_out, capacity, count_out, tile_starts_out);
 }
 
 struct SparseLists {
@@ -406,6 +523,45 @@ gq_status gq_compact(const void *levels, int64_t d, const gq_params *p, uint32_t
         if (launched() != GQ_OK) return GQ_ERR_DEVICE;
     }
     return GQ_OK;
+}
+
+gq_status gq_quantize_compact(const float *x, int64_t d, const float *norm, const gq_params *p, uint32_t worker, int64_t index_base,
+                              uint32_t *indices_out, int8_t *values_out, int64_t capacity, uint64_t *count_out,
+                              uint32_t *tile_starts_out, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    const gq_status st = check_params(p, true, false);
+    if (st != GQ_OK) return st;
+    if (p->pack != GQ_PACK_I8) return GQ_ERR_UNSUPPORTED;
+    const bool half = short_draws(p);
+    if (d < 0 || d > 0xFFFFFFFFLL || capacity < 0 || index_base < 0 || (index_base & (half ? 7 : 3)) != 0) return GQ_ERR_INVALID_ARG;
+    if (!aligned(norm, 4) || !aligned(count_out, 8)) return GQ_ERR_INVALID_ARG;
+    if (d > 0 && !aligned(x, 16)) return GQ_ERR_INVALID_ARG;
+    if (capacity > 0 && (!aligned(indices_out, 4) || !values_out)) return GQ_ERR_INVALID_ARG;
+    if (tile_starts_out && !aligned(tile_starts_out, 4)) return GQ_ERR_INVALID_ARG;
+    if (!workspace || workspace_bytes < gq_compact_workspace_bytes(d)) return GQ_ERR_WORKSPACE;
+    if (!aligned(workspace, 8)) return GQ_ERR_INVALID_ARG;
+    hipStream_t hs = (hipStream_t)hip_stream;
+    uint64_t *state = reinterpret_cast<uint64_t *>(workspace);
+    const int64_t blocks = (d + kCompactSpan - 1) / kCompactSpan;
+    if (!grid_fits(blocks, kCompactBlock)) return GQ_ERR_INVALID_ARG;
+    const int64_t words = 2 + blocks + (blocks + kGroupBlocks - 1) / kGroupBlocks;
+    hipLaunchKernelGGL(compact_clear_kernel, dim3((unsigned)((words + kBlock - 1) / kBlock)), dim3(kBlock), 0, hs, state, words, count_out,
+                       blocks == 0 ? tile_starts_out : nullptr);
+    if (launched() != GQ_OK) return GQ_ERR_DEVICE;
+    if (blocks == 0) return GQ_OK;
+    const int lane_vecs = half ? 2 : 1;                                  // vectors per Philox call
+    const uint64_t call_base = (uint64_t)index_base / (uint64_t)(4 * lane_vecs);
+    // the high counter word is a scalar unless the gradient (rounded up to whole spans) crosses 2^32 calls
+    const bool one_stretch = ((call_base & 0xFFFFFFFFull) + (uint64_t)(blocks * (kCompactSpan / 4) / lane_vecs)) <= ((uint64_t)1 << 32);
+#define GQ_QC(SC, UH, HF) hipLaunchKernelGGL((quantize_compact_kernel<SC, UH, HF>), dim3((unsigned)blocks), dim3(kCompactBlock), 0, hs, x, d, \
+                                             norm, p->s, p->seed, worker, call_base, state, blocks, indices_out, values_out, capacity, \
+                                             count_out, tile_starts_out)
+#define GQ_QC2(SC, UH) do { if (half) GQ_QC(SC, UH, true); else GQ_QC(SC, UH, false); } while (0)
+    if (p->scheme == GQ_LINEAR) { if (one_stretch) GQ_QC2(0, true); else GQ_QC2(0, false); }
+    else                        { if (one_stretch) GQ_QC2(1, true); else GQ_QC2(1, false); }
+#undef GQ_QC2
+#undef GQ_QC
+    return launched();
 }
 
 gq_status gq_sparse_aggregate(const uint32_t *const *indices, const int8_t *const *values,

@@ -760,6 +760,109 @@ def test_compact_errors():
     assert int(cnt.item()) == 0
 
 
+def check_quantize_compact(x, xh, nf, norm_t, scheme, s, seed, worker, base, rng_bits):
+    """gq_quantize_compact against the oracle's quantisation followed by its compaction: count, list, tile starts, guards."""
+    d = x.numel()
+    p = gq.make_params(SCHEMES[scheme], s, 0, 0, seed=seed, rng_bits=rng_bits)
+    q = O.quantize(xh, nf, SCHEMES[scheme], s, seed, worker, base, rng_bits=rng_bits)
+    n, widx, wval = O.compact(q)
+    cap = n + 7
+    idx = torch.full((cap,), -1, dtype=torch.int32, device=DEV)
+    val = torch.full((cap,), 0x5A, dtype=torch.int8, device=DEV)
+    cnt = torch.full((1,), -1, dtype=torch.int64, device=DEV)
+    nts = gq.tile_starts_len(d)
+    starts = torch.full((nts + 4,), -1, dtype=torch.int32, device=DEV)
+    gq.quantize_compact(x, norm_t, p, worker, base, idx, val, cnt, tile_starts_out=starts)
+    torch.cuda.synchronize()
+    assert int(cnt.item()) == n
+    gi, gv = host(idx).view(np.uint32), host(val)
+    assert np.array_equal(gi[:n], widx) and np.array_equal(gv[:n].astype(np.int32), wval)
+    assert np.all(gi[n:] == 0xFFFFFFFF) and np.all(gv[n:] == 0x5A)
+    gs = host(starts).view(np.uint32)
+    assert np.array_equal(gs[:nts], np.searchsorted(widx.astype(np.int64), 4096 * np.arange(nts, dtype=np.int64)).astype(np.uint32))
+    assert np.all(gs[nts:] == 0xFFFFFFFF)
+    return n
+
+
+@pytest.mark.parametrize("rng_bits", [32, 16])
+@pytest.mark.parametrize("scheme,s,kind", [("linear", 127, "linf"), ("linear", 15, "l2"), ("exp", 7, "l2"), ("exp", 16, "linf")])
+@pytest.mark.parametrize("d", [1, 5, 4095, 4097, 32_768, 32_771, 70_001, 1_048_579])
+def test_quantize_compact_matches_oracle(scheme, s, kind, d, rng_bits):
+    # the sender without dense codes: one span, a ragged span, many spans with a ragged tail; a bucket offset
+    x = gaussians(1, d, seed=d + s)[0]
+    xh = host(x)
+    _, nf, _ = oracle_norm([x], NORMS[kind])
+    norm_t = dev_scalar(float(nf))
+    total = 0
+    for worker, base in ((0, 0), (3, 8 * 12_345)):
+        total += check_quantize_compact(x, xh, nf, norm_t, scheme, s, 777, worker, base, rng_bits)
+    if d >= 4095:
+        assert total > 0
+
+
+def test_quantize_compact_bucket_offsets_unusable_norm_and_short_buffers():
+    d = 100_003
+    x = gaussians(1, d, seed=5)[0]
+    xh = host(x)
+    _, nf, _ = oracle_norm([x], NORMS["linf"])
+    norm_t = dev_scalar(float(nf))
+    # the Philox call index crosses a multiple of 2^32 inside the gradient (full draws: 2^34 coordinates, short: 2^35)
+    for rng_bits, top in ((32, 1 << 34), (16, 1 << 35)):
+        for base in (top - 8 * 1000, top - 8, top, 3 * top - 8 * 9_000):
+            check_quantize_compact(x, xh, nf, norm_t, "linear", 127, 31337, 2, base, rng_bits)
+            check_quantize_compact(x, xh, nf, norm_t, "exp", 12, 31337, 2, base, rng_bits)
+    # the same list as gq_quantize followed by gq_compact on the GPU
+    p = gq.make_params(0, 127, 0, 0, seed=9)
+    lv = gpu_quantize(x, norm_t, p, 1, 64)[0]
+    n_max = d
+    outs = []
+    for call in ("two", "one"):
+        idx = torch.zeros(n_max, dtype=torch.int32, device=DEV); val = torch.zeros(n_max, dtype=torch.int8, device=DEV)
+        cnt = torch.zeros(1, dtype=torch.int64, device=DEV); st = torch.zeros(gq.tile_starts_len(d), dtype=torch.int32, device=DEV)
+        if call == "two":
+            gq.compact(lv, d, p, idx, val, cnt, tile_starts_out=st)
+        else:
+            gq.quantize_compact(x, norm_t, p, 1, 64, idx, val, cnt, tile_starts_out=st)
+        outs.append((idx, val, cnt, st))
+    torch.cuda.synchronize()
+    for a, b in zip(outs[0], outs[1]):
+        assert torch.equal(a, b)
+    n = int(outs[0][2].item())
+    # a list buffer that is too short: the true count, the first entries, nothing beyond
+    idx2 = torch.full((3 + 4,), -1, dtype=torch.int32, device=DEV); val2 = torch.full((3 + 4,), 0x5A, dtype=torch.int8, device=DEV)
+    cnt2 = torch.zeros(1, dtype=torch.int64, device=DEV)
+    gq.quantize_compact(x, norm_t, p, 1, 64, idx2[:3], val2[:3], cnt2)
+    torch.cuda.synchronize()
+    assert int(cnt2.item()) == n and torch.equal(idx2[:3], outs[0][0][:3]) and bool((idx2[3:] == -1).all()) and bool((val2[3:] == 0x5A).all())
+    # an unusable norm: no entries; NaN coordinates under a usable norm follow the oracle
+    for bad in (0.0, float("nan"), float("inf")):
+        cnt3 = torch.full((1,), -1, dtype=torch.int64, device=DEV)
+        gq.quantize_compact(x, dev_scalar(bad), p, 0, 0, idx2[:3], val2[:3], cnt3)
+        torch.cuda.synchronize()
+        assert int(cnt3.item()) == 0
+    xn = x.clone(); xn[17] = float("nan"); xn[4099] = float("inf"); xn[d - 1] = float("-inf")
+    check_quantize_compact(xn, host(xn), nf, norm_t, "linear", 127, 9, 0, 0, 32)
+    check_quantize_compact(xn, host(xn), nf, norm_t, "exp", 7, 9, 0, 0, 16)
+    # argument errors
+    with pytest.raises(gq.GQError) as e:
+        gq.quantize_compact(x, norm_t, gq.make_params(0, 7, PACKS["i4"]), 0, 0, idx2, val2, cnt2)
+    assert e.value.status == gq.GQ_ERR_UNSUPPORTED
+    with pytest.raises(gq.GQError) as e:
+        gq.quantize_compact(x, norm_t, p, 0, 2, idx2, val2, cnt2)
+    assert e.value.status == gq.GQ_ERR_INVALID_ARG
+    with pytest.raises(gq.GQError) as e:
+        gq.quantize_compact(x, norm_t, gq.make_params(0, 127, rng_bits=16), 0, 4, idx2, val2, cnt2)
+    assert e.value.status == gq.GQ_ERR_INVALID_ARG
+    with pytest.raises(gq.GQError) as e:
+        gq.quantize_compact(x, norm_t, p, 0, 0, idx2, val2, cnt2, workspace=torch.zeros(8, dtype=torch.uint8, device=DEV))
+    assert e.value.status == gq.GQ_ERR_WORKSPACE
+    empty = torch.zeros(0, dtype=torch.float32, device=DEV)
+    cnt4 = torch.full((1,), -1, dtype=torch.int64, device=DEV)
+    gq.quantize_compact(empty, norm_t, p, 0, 0, idx2, val2, cnt4)
+    torch.cuda.synchronize()
+    assert int(cnt4.item()) == 0
+
+
 @pytest.mark.parametrize("scheme,s,kind", [("linear", 15, "l2"), ("linear", 127, "linf"), ("exp", 7, "l2")])
 @pytest.mark.parametrize("K,d", [(1, 1000), (4, 70_001), (16, 300_000)])
 def test_sparse_path_equals_dense_aggregate(scheme, s, kind, K, d):
