@@ -99,6 +99,9 @@ template <int NPAD, int PER> __device__ __forceinline__ constexpr bool first_of_
     return NPAD == 2 ? node == 1 : (PER == 2 ? node == 1 : node == 2);
 }
 
+// leaf w0 + j as a compile-time constant
+template <int W0, int J> using jj_leaf = std::integral_constant<int, W0 + J>;
+
 template <int NPAD, bool UNIFORM_HI, int W>
 __global__ void __launch_bounds__(kReduceBlock)
 exp_reduce_kernel(LevelCPtrs Lv, int K, int64_t d, int s, uint64_t seed, uint64_t call_base,
@@ -145,54 +148,81 @@ exp_reduce_kernel(LevelCPtrs Lv, int K, int64_t d, int s, uint64_t seed, uint64_
     // the Philox words of the node groups in use, one slot per tree level; the binary32 path keeps them complemented
     uint32_t grp[L + 1][4];
     constexpr int kBatch = NPAD < 8 ? NPAD : 8;
-    static_for<0, NPAD / kBatch>([&](auto batch) {
-        constexpr int w0 = decltype(batch)::value * kBatch;
-        uint32_t words[kBatch];
+    constexpr int kBatchL = NPAD < 8 ? L : 3;                // tree levels inside a batch of leaves
+    // the node above the subtree of 2^lvl leaves that ends with leaf i
+    auto fold = [&](auto leaf, auto level) {
+        constexpr int i = decltype(leaf)::value, lvl = decltype(level)::value;
+        if constexpr (((i + 1) & ((1 << lvl) - 1)) == 0) {               // the subtree is complete
+            constexpr int top = __builtin_popcount((unsigned)i) - (lvl - 1);   // one partial result was folded per level below
+            constexpr int node = (NPAD >> lvl) + (i >> lvl);             // heap numbering
+            // the root shares its group with nodes 2 and 3 (one level down) when a call serves four nodes
+            constexpr int slot = (PER == 4 && node == 1 && NPAD >= 4) ? lvl - 1 : lvl;
+            if constexpr (first_of_group<NPAD, PER>(node)) {
+                const Words4 r = philox4x32_10(c_lo, c_hi, (uint32_t)(node / PER), 1u, k0, k1);
 #pragma unroll
-        for (int j = 0; j < kBatch; j++) words[j] = fetch(w0 + j);
-        static_for<0, kBatch>([&](auto jj) {
-            constexpr int j = decltype(jj)::value;
-            constexpr int i = w0 + j;                        // leaf index; the stack depth is popcount(i)
-            constexpr int top0 = __builtin_popcount((unsigned)i);
+                for (int c = 0; c < 4; c++) grp[slot][c] = kFloat ? ~r.w[c] : r.w[c];
+            }
 #pragma unroll
             for (int c = 0; c < 4; c++) {
                 if constexpr (kFloat) {
-                    st_f[top0][c] = leaf_value[(words[j] >> (8 * c)) & 255u];
+                    // the top s bits of the node's complemented field, moved to the top of the mantissa
+                    const uint32_t A = __builtin_amdgcn_ubfe(grp[slot][c], (uint32_t)(W * (node % PER) + W - s), (uint32_t)s)
+                                       << (23 - s);
+                    st_f[top - 1][c] = alg2_pair_f32(st_f[top - 1][c], st_f[top][c], A);
                 } else {
-                    // code k >= 1 of the exponential grid -> e = s - k + 1 + L; code 0 is zero
-                    const int q = (int)(int8_t)(words[j] >> (8 * c));
-                    st_sg[top0][c] = q;
-                    st_e[top0][c] = q ? s + 1 + L - abs(q) : kZeroE;
+                    const Pow2 o = alg2_pair_int(Pow2{st_sg[top - 1][c], st_e[top - 1][c]}, Pow2{st_sg[top][c], st_e[top][c]},
+                                                 grp[slot][c], s);
+                    st_sg[top - 1][c] = o.sg; st_e[top - 1][c] = o.e;
                 }
             }
-            static_for<1, L + 1>([&](auto ll) {
-                constexpr int lvl = decltype(ll)::value;
-                if constexpr (((i + 1) & ((1 << lvl) - 1)) == 0) {       // a subtree of 2^lvl leaves is complete
-                    constexpr int top = top0 - (lvl - 1);                // one partial result was folded per level below
-                    constexpr int node = (NPAD >> lvl) + (i >> lvl);     // heap numbering
-                    // the root shares its group with nodes 2 and 3 (one level down) when a call serves four nodes
-                    constexpr int slot = (PER == 4 && node == 1 && NPAD >= 4) ? lvl - 1 : lvl;
-                    if constexpr (first_of_group<NPAD, PER>(node)) {
-                        const Words4 r = philox4x32_10(c_lo, c_hi, (uint32_t)(node / PER), 1u, k0, k1);
+        }
+    };
+    static_for<0, NPAD / kBatch>([&](auto batch) {
+        constexpr int w0 = decltype(batch)::value * kBatch;
+        // A batch of leaves beyond the last worker is a zero subtree: its root is set, not computed (K > NPAD / 2, so
+        // only batches of the second half can be empty; the draws of their inner nodes are needed by nobody else).
+        if (2 * w0 < NPAD || w0 < K) {
+            uint32_t words[kBatch];
 #pragma unroll
-                        for (int c = 0; c < 4; c++) grp[slot][c] = kFloat ? ~r.w[c] : r.w[c];
-                    }
+            for (int j = 0; j < kBatch; j++) words[j] = fetch(w0 + j);
+            static_for<0, kBatch>([&](auto jj) {
+                constexpr int j = decltype(jj)::value;
+                constexpr int i = w0 + j;                    // leaf index; the stack depth is popcount(i)
+                constexpr int top0 = __builtin_popcount((unsigned)i);
 #pragma unroll
-                    for (int c = 0; c < 4; c++) {
-                        if constexpr (kFloat) {
-                            // the top s bits of the node's complemented field, moved to the top of the mantissa
-                            const uint32_t A = __builtin_amdgcn_ubfe(grp[slot][c], (uint32_t)(W * (node % PER) + W - s), (uint32_t)s)
-                                               << (23 - s);
-                            st_f[top - 1][c] = alg2_pair_f32(st_f[top - 1][c], st_f[top][c], A);
-                        } else {
-                            const Pow2 o = alg2_pair_int(Pow2{st_sg[top - 1][c], st_e[top - 1][c]}, Pow2{st_sg[top][c], st_e[top][c]},
-                                                         grp[slot][c], s);
-                            st_sg[top - 1][c] = o.sg; st_e[top - 1][c] = o.e;
-                        }
+                for (int c = 0; c < 4; c++) {
+                    if constexpr (kFloat) {
+                        st_f[top0][c] = leaf_value[(words[j] >> (8 * c)) & 255u];
+                    } else {
+                        // code k >= 1 of the exponential grid -> e = s - k + 1 + L; code 0 is zero
+                        const int q = (int)(int8_t)(words[j] >> (8 * c));
+                        st_sg[top0][c] = q;
+                        st_e[top0][c] = q ? s + 1 + L - abs(q) : kZeroE;
                     }
                 }
+                static_for<1, kBatchL + 1>([&](auto ll) { fold(jj_leaf<w0, j>(), ll); });
             });
-        });
+        } else {
+            constexpr int top0 = __builtin_popcount((unsigned)w0);
+#pragma unroll
+            for (int c = 0; c < 4; c++) {
+                if constexpr (kFloat) {
+                    st_f[top0][c] = 0.0f;
+                } else {
+                    st_sg[top0][c] = 0;
+                    st_e[top0][c] = kZeroE;
+                }
+            }
+        }
+        // the batch's result is pinned: without this the compiler issues the loads of all NPAD workers before the first
+        // node (one register each), and trees of 64 leaves run with two waves per SIMD
+        if constexpr (NPAD > kBatch) {
+            constexpr int t0 = __builtin_popcount((unsigned)w0);
+            if constexpr (kFloat) asm volatile("" : "+v"(st_f[t0][0]), "+v"(st_f[t0][1]), "+v"(st_f[t0][2]), "+v"(st_f[t0][3]) : : "memory");
+            else asm volatile("" : "+v"(st_e[t0][0]), "+v"(st_e[t0][1]), "+v"(st_e[t0][2]), "+v"(st_e[t0][3]),
+                                   "+v"(st_sg[t0][0]), "+v"(st_sg[t0][1]), "+v"(st_sg[t0][2]), "+v"(st_sg[t0][3]) : : "memory");
+        }
+        static_for<kBatchL + 1, L + 1>([&](auto ll) { fold(jj_leaf<w0, kBatch - 1>(), ll); });
     });
     int root[4];                                            // sign * e of the root, 0 for zero
 #pragma unroll
@@ -281,38 +311,55 @@ exp_reduce_f16_kernel(LevelCPtrs Lv, int K, int64_t d, int s, uint64_t seed, uin
     f16x2 st[L + 1][2];                                      // the stack: coordinates (0,1) and (2,3) of every partial result
     uint32_t grp[L + 1][4];                                  // masked complemented Philox words of the node groups in use
     constexpr int kBatch = NPAD < 8 ? NPAD : 8;
+    constexpr int kBatchL = NPAD < 8 ? L : 3;                // tree levels inside a batch of leaves
+    // the node above the subtree of 2^lvl leaves that ends with leaf i
+    auto fold = [&](auto leaf, auto level) {
+        constexpr int i = decltype(leaf)::value, lvl = decltype(level)::value;
+        if constexpr (((i + 1) & ((1 << lvl) - 1)) == 0) {               // the subtree is complete
+            constexpr int top = __builtin_popcount((unsigned)i) - (lvl - 1);   // one partial result was folded per level below
+            constexpr int node = (NPAD >> lvl) + (i >> lvl);             // heap numbering
+            constexpr int slot = (node == 1 && NPAD >= 4) ? lvl - 1 : lvl;     // the root shares its group with nodes 2 and 3
+            if constexpr (first_of_group<NPAD, PER>(node)) {
+                const Words4 r = philox4x32_10(c_lo, c_hi, (uint32_t)(node / PER), 1u, k0, k1);
+#pragma unroll
+                for (int c = 0; c < 4; c++) grp[slot][c] = ~r.w[c] & keep;
+            }
+            // byte `node % 4` of the words of coordinates (0,1) resp. (2,3) into the low bytes of the two halves
+            constexpr uint32_t kZero = 0x0Cu;                // v_perm_b32 selector of a zero byte
+            constexpr uint32_t sel = (kZero << 24) | ((uint32_t)(4 + node % PER) << 16) | (kZero << 8) | (uint32_t)(node % PER);
+            const uint32_t A01 = __builtin_amdgcn_perm(grp[slot][1], grp[slot][0], sel) << 2;
+            const uint32_t A23 = __builtin_amdgcn_perm(grp[slot][3], grp[slot][2], sel) << 2;
+            st[top - 1][0] = alg2_pair_f16x2(st[top - 1][0], st[top][0], A01);
+            st[top - 1][1] = alg2_pair_f16x2(st[top - 1][1], st[top][1], A23);
+        }
+    };
     static_for<0, NPAD / kBatch>([&](auto batch) {
         constexpr int w0 = decltype(batch)::value * kBatch;
-        uint32_t words[kBatch];
+        // A batch of leaves beyond the last worker is a zero subtree: its root is set, not computed (K > NPAD / 2, so
+        // only batches of the second half can be empty; the draws of their inner nodes are needed by nobody else).
+        if (2 * w0 < NPAD || w0 < K) {
+            uint32_t words[kBatch];
 #pragma unroll
-        for (int j = 0; j < kBatch; j++) words[j] = fetch(w0 + j);
-        static_for<0, kBatch>([&](auto jj) {
-            constexpr int j = decltype(jj)::value;
-            constexpr int i = w0 + j;                        // leaf index; the stack depth is popcount(i)
-            constexpr int top0 = __builtin_popcount((unsigned)i);
-            st[top0][0] = (f16x2){leaf_value[words[j] & 255u], leaf_value[(words[j] >> 8) & 255u]};
-            st[top0][1] = (f16x2){leaf_value[(words[j] >> 16) & 255u], leaf_value[words[j] >> 24]};
-            static_for<1, L + 1>([&](auto ll) {
-                constexpr int lvl = decltype(ll)::value;
-                if constexpr (((i + 1) & ((1 << lvl) - 1)) == 0) {       // a subtree of 2^lvl leaves is complete
-                    constexpr int top = top0 - (lvl - 1);                // one partial result was folded per level below
-                    constexpr int node = (NPAD >> lvl) + (i >> lvl);     // heap numbering
-                    constexpr int slot = (node == 1 && NPAD >= 4) ? lvl - 1 : lvl;   // the root shares its group with nodes 2 and 3
-                    if constexpr (first_of_group<NPAD, PER>(node)) {
-                        const Words4 r = philox4x32_10(c_lo, c_hi, (uint32_t)(node / PER), 1u, k0, k1);
-#pragma unroll
-                        for (int c = 0; c < 4; c++) grp[slot][c] = ~r.w[c] & keep;
-                    }
-                    // byte `node % 4` of the words of coordinates (0,1) resp. (2,3) into the low bytes of the two halves
-                    constexpr uint32_t kZero = 0x0Cu;        // v_perm_b32 selector of a zero byte
-                    constexpr uint32_t sel = (kZero << 24) | ((uint32_t)(4 + node % PER) << 16) | (kZero << 8) | (uint32_t)(node % PER);
-                    const uint32_t A01 = __builtin_amdgcn_perm(grp[slot][1], grp[slot][0], sel) << 2;
-                    const uint32_t A23 = __builtin_amdgcn_perm(grp[slot][3], grp[slot][2], sel) << 2;
-                    st[top - 1][0] = alg2_pair_f16x2(st[top - 1][0], st[top][0], A01);
-                    st[top - 1][1] = alg2_pair_f16x2(st[top - 1][1], st[top][1], A23);
-                }
+            for (int j = 0; j < kBatch; j++) words[j] = fetch(w0 + j);
+            static_for<0, kBatch>([&](auto jj) {
+                constexpr int j = decltype(jj)::value;
+                constexpr int top0 = __builtin_popcount((unsigned)(w0 + j));     // leaf w0 + j; the stack depth is popcount of it
+                st[top0][0] = (f16x2){leaf_value[words[j] & 255u], leaf_value[(words[j] >> 8) & 255u]};
+                st[top0][1] = (f16x2){leaf_value[(words[j] >> 16) & 255u], leaf_value[words[j] >> 24]};
+                static_for<1, kBatchL + 1>([&](auto ll) { fold(jj_leaf<w0, j>(), ll); });
             });
-        });
+        } else {
+            constexpr int top0 = __builtin_popcount((unsigned)w0);
+            st[top0][0] = (f16x2){(_Float16)0, (_Float16)0};
+            st[top0][1] = (f16x2){(_Float16)0, (_Float16)0};
+        }
+        // the batch's result is pinned: without this the compiler issues the loads of all NPAD workers before the first
+        // node (one register each), and trees of 64 leaves run with two waves per SIMD
+        if constexpr (NPAD > kBatch) {
+            constexpr int t0 = __builtin_popcount((unsigned)w0);
+            asm volatile("" : "+v"(st[t0][0]), "+v"(st[t0][1]) : : "memory");
+        }
+        static_for<kBatchL + 1, L + 1>([&](auto ll) { fold(jj_leaf<w0, kBatch - 1>(), ll); });
     });
     int root[4];                                            // sign * e of the root, 0 for zero
 #pragma unroll

@@ -603,7 +603,7 @@ def test_short_draws_buckets_boundary_and_separate_calls():
 
 
 # ------------------------------------------------------------------------------------ Algorithm 2
-@pytest.mark.parametrize("K", [1, 2, 3, 4, 5, 8, 13, 16, 32, 33, 64])
+@pytest.mark.parametrize("K", [1, 2, 3, 4, 5, 8, 13, 16, 17, 24, 25, 32, 33, 41, 48, 56, 64])
 @pytest.mark.parametrize("s,d", [(7, 70_003), (16, 4099), (31, 1021), (1, 255), (8, 4098), (9, 515)])
 def test_exp_reduce_matches_oracle(K, s, d):
     # the paper's reduce function for exponential dithering, tree order: reduced (sign, e) bit-exact,
