@@ -221,14 +221,19 @@ gq_status gq_bucketed_quantize_aggregate(const float *const *x /* host */, int K
  * rounded up to a power of two (the paper's division by 2n keeps every partial sum within 1/2), and
  * reduced pairwise in tree order: nodes numbered as a binary heap (root 1, children 2h and 2h+1, worker i
  * is leaf n'+i, missing workers are zeros, operand 1 is child 2h); every node rounds its sum to a
- * neighbouring power of two, upwards iff k > diff as in the listing, with k = 1 + (leading zero bits of
- * the 32-bit Philox word of counter (lo32(g/4), hi32(g/4), node, 1), word g mod 4), so that P(k > b) = 2^-b.
+ * neighbouring power of two, upwards iff k > diff as in the listing.  k follows the listing's first statement
+ * with m = s + 1 and p = r / 2^s for an s-bit random integer r: k = s - floor(log2 r), and k = m for r = 0, so
+ * that P(k > b) = 2^-b for b < m.  The s bits of node h at coordinate g are the top s bits of field h mod (32/W)
+ * (counted from the low end) of word g mod 4 of the Philox call with counter (lo32(g/4), hi32(g/4), h / (32/W), 1),
+ * W = 8 for s <= 8, 16 for s <= 16, else 32: one call serves the four coordinates of 32/W nodes.
  *   levels       host array of K device int8[d] code buffers
  *   reduced_out  device int8[d]: sign * e of the root (0 for zero), or NULL
  *   dequant_out  device fp32[d]: the mean it stands for, sign * 2^-e * 2n' * norm / K, or NULL
  *   norm         device fp32[1]; read only if dequant_out is given
  * p->pack and p->agg are ignored; p->scheme must be GQ_EXP (else GQ_ERR_UNSUPPORTED).  The result is
- * unbiased for the exact sum and adds at most a factor 9/8 of second moment per tree level. */
+ * unbiased for the exact sum wherever no pair of operands is further apart than the cap on k reaches (gap < m
+ * for equal signs; beyond it the smaller operand, at most 2^-(s+1) of the larger, is dropped), and adds at most a
+ * factor 9/8 of second moment per tree level. */
 gq_status gq_exp_reduce(const void *const *levels /* host */, int K, int64_t d, const gq_params *p /* host */,
                         int64_t index_base, const float *norm, void *reduced_out, float *dequant_out,
                         void *hip_stream);

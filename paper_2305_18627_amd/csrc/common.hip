@@ -11,7 +11,7 @@ using namespace gq;
 
 extern "C" {
 
-int gq_version(void) { return 1003; }
+int gq_version(void) { return 1004; }
 
 const char *gq_status_string(gq_status st)
 {
