@@ -202,11 +202,6 @@ def time_rows(gq, torch, xs, norm, params, cfg, args):
             rows["sparse_aggregate"] = timed(lambda: gq.sparse_aggregate(idxs, vals, cnts, d, p, agg, tile_starts=tabs), 4.0 * d + 5.0 * tot)
             rows["sparse_aggregate_searching"] = timed(lambda: gq.sparse_aggregate(idxs, vals, cnts, d, p, agg), 4.0 * d + 5.0 * tot)
         rows["nonzero_fraction"] = tot / (float(K) * d)
-    # context for the kernels that write a large share of their bytes: what this chip does on a plain device-to-device
-    # copy (half reads, half writes), bytes counted both ways
-    src = xs[0][: min(d, 1 << 28)]
-    dst = torch.empty_like(src)
-    rows["plain_copy_torch"] = timed(lambda: dst.copy_(src), 8.0 * src.numel())
     rows["formats"] = {"pack": cfg["pack"], "agg": cfg["agg"]}
     return rows
 

@@ -261,6 +261,15 @@ def test_workload_c3_sparse_branch_at_full_size(kind):
         assert n == int(torch.count_nonzero(lvs[i]))
         # the table of tile starts is the position of every multiple of 4096 in the (oracle-checked) index list
         assert torch.equal(tab.to(torch.int64) & 0xFFFFFFFF, torch.searchsorted(idx[:n].to(torch.int64) & 0xFFFFFFFF, edges))
+        # the sender without stored codes: count, list (with guards behind it) and table, bit for bit those of the two calls
+        idx1 = torch.full((n + 8,), -1, dtype=torch.int32, device=DEV)
+        val1 = torch.full((n + 8,), 0x5A, dtype=torch.int8, device=DEV)
+        cnt1 = torch.full((1,), -1, dtype=torch.int64, device=DEV)
+        tab1 = torch.full((gq.tile_starts_len(d),), -1, dtype=torch.int32, device=DEV)
+        gq.quantize_compact(xs[i], norm_t, p, i, 0, idx1, val1, cnt1, ws, tile_starts_out=tab1)
+        torch.cuda.synchronize()
+        assert int(cnt1.item()) == n and torch.equal(idx1, idx) and torch.equal(val1, val) and torch.equal(tab1, tab), i
+        del idx1, val1, tab1
         if i in (0, K - 1):
             # the sender in full against the oracle: its own codes from the same gradient, its own list
             q = O.quantize(host(xs[i]), nf, O.LINEAR, s, SI.QUANT_SEED, i, 0)
