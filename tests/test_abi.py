@@ -188,6 +188,14 @@ def test_argument_checks_need_no_device(gq):
     assert cp(ok, ts=C.c_void_p(0x1002)) == I
     assert cp(ok, cap=-1) == I and cp(ok, cnt=None) == I and cp(ok, cnt=odd) == I
     assert cp(ok, ws=None) == gq.GQ_ERR_WORKSPACE and cp(ok, d=1 << 20, wsb=8) == gq.GQ_ERR_WORKSPACE
+    # the sender straight from the gradient: the argument checks of gq_quantize and of gq_compact together
+    qc = lambda p, x=fake, d=64, norm=fake, base=0, cap=16, cnt=fake, ws=fake, wsb=1024, ts=None: \
+        lib.gq_quantize_compact(x, d, norm, C.byref(p), 0, base, fake, fake, cap, cnt, ts, ws, wsb, None)
+    assert qc(av) == gq.GQ_ERR_UNSUPPORTED and qc(ok, x=odd) == I and qc(ok, d=-1) == I and qc(ok, d=1 << 33) == I
+    assert qc(ok, norm=None) == I and qc(ok, base=2) == I and qc(ok, base=-4) == I
+    assert qc(P(gq.GQ_LINEAR, 127, rng_bits=16), base=4) == I                                   # short draws: multiples of 8
+    assert qc(ok, ts=C.c_void_p(0x1002)) == I and qc(ok, cap=-1) == I and qc(ok, cnt=None) == I and qc(ok, cnt=odd) == I
+    assert qc(ok, ws=None) == gq.GQ_ERR_WORKSPACE and qc(ok, d=1 << 20, wsb=8) == gq.GQ_ERR_WORKSPACE
     caps = (C.c_int64 * 2)(4, 4)
     sa = lambda p, K=2, idx=arr, d=64, agg=fake, ts=None: lib.gq_sparse_aggregate(idx, arr, arr, caps, ts, K, d, C.byref(p), agg, None)
     assert sa(ok, ts=(C.c_void_p * 2)(0x1000, 0x2002)) == I
