@@ -203,6 +203,25 @@ constexpr int kDppQuadXor2 = 0x4E;     // quad_perm:[2,3,0,1]
 constexpr int kDppHalfMirror = 0x141;  // row_half_mirror: lane i <-> 7-i of each 8
 constexpr int kDppMirror = 0x140;      // row_mirror:      lane i <-> 15-i of each 16
 
+// Short draws (16 random bits per coordinate): one Philox call serves the eight coordinates of two
+// neighbouring vectors 2c and 2c+1.  To keep every load and store of a wave contiguous, a wave takes 128
+// consecutive vectors and lane l owns vectors l ("A") and 64 + l ("B") of them.  Even lane 2i runs the call
+// of vectors 2i, 2i+1 of the A half, odd lane 2i+1 the call of vectors 2i, 2i+1 of the B half, and the two
+// lanes swap the half of the words the other needs (one DPP exchange of two registers).  Afterwards
+// word pair `a` rounds the lane's A vector and `b` its B vector; coordinate j of a vector takes the low
+// (j even) or high (j odd) half of word j / 2 of its pair, moved to the top of a 32-bit word with zeros
+// below, so that the rounding rules apply unchanged.  Every lane of the wave must be active.
+struct ShortDraws { uint32_t a[2], b[2]; };
+__device__ __forceinline__ ShortDraws share_short_draws(const Words4 &r, bool odd)
+{
+    const uint32_t got0 = dpp32<kDppQuadXor1>(odd ? r.w[0] : r.w[2]);
+    const uint32_t got1 = dpp32<kDppQuadXor1>(odd ? r.w[1] : r.w[3]);
+    ShortDraws o;
+    o.a[0] = odd ? got0 : r.w[0]; o.a[1] = odd ? got1 : r.w[1];
+    o.b[0] = odd ? r.w[2] : got0; o.b[1] = odd ? r.w[3] : got1;
+    return o;
+}
+
 __device__ __forceinline__ double wave_sum(double v)
 {
     v += dpp64<kDppQuadXor1>(v);

@@ -121,25 +121,6 @@ constexpr int kWindowMinWorkers = 8;
 constexpr double kWindowMinLoads = 2.5e8;         // K * d from which the windows win (measured)
 constexpr int kWindowMaxPolls = 1024;             // polls of about 0.2 us each: the longest period (K = 64, short draws) is 79 us
 
-// Short draws (16 random bits per coordinate): one Philox call serves the eight coordinates of two
-// neighbouring vectors 2c and 2c+1.  To keep every load and store of a wave contiguous, a wave takes 128
-// consecutive vectors and lane l owns vectors l ("A") and 64 + l ("B") of them.  Even lane 2i runs the call
-// of vectors 2i, 2i+1 of the A half, odd lane 2i+1 the call of vectors 2i, 2i+1 of the B half, and the two
-// lanes swap the half of the words the other needs (one DPP exchange of two registers).  Afterwards
-// word pair `a` rounds the lane's A vector and `b` its B vector; coordinate j of a vector takes the low
-// (j even) or high (j odd) half of word j / 2 of its pair, moved to the top of a 32-bit word with zeros
-// below, so that the rounding rules apply unchanged.  Every lane of the wave must be active.
-struct ShortDraws { uint32_t a[2], b[2]; };
-__device__ __forceinline__ ShortDraws share_short_draws(const Words4 &r, bool odd)
-{
-    const uint32_t got0 = dpp32<kDppQuadXor1>(odd ? r.w[0] : r.w[2]);
-    const uint32_t got1 = dpp32<kDppQuadXor1>(odd ? r.w[1] : r.w[3]);
-    ShortDraws o;
-    o.a[0] = odd ? got0 : r.w[0]; o.a[1] = odd ? got1 : r.w[1];
-    o.b[0] = odd ? r.w[2] : got0; o.b[1] = odd ? r.w[3] : got1;
-    return o;
-}
-
 // The launch covers the vectors v0 <= v < vend of the buffers (HALF: v0 = 0).  With UNIFORM_HI the host
 // guarantees that the Philox call index does not cross a multiple of 2^32 inside the launch, so the high
 // counter word is a scalar: the first round and half of the second are then shared by all lanes or all

@@ -288,7 +288,8 @@ compact_onepass_kernel(const uint8_t *__restrict__ lv, int64_t d, uint64_t *__re
 // passes the code words of a tile through LDS so that every thread ends up with 16 consecutive codes, and hands the
 // span to emit_span: 4 d bytes read, 5 nnz written, and the codes never reach memory.
 //   full draws   a thread owns vectors t, t + 256, t + 512, t + 768 of a tile (a wave reads 1 KiB per load)
-//   short draws  a thread owns the vector pairs of calls t and t + 256 of a tile (one Philox call per eight coordinates)
+//   short draws  a lane owns vectors l and 64 + l of two chunks of 128 vectors and shares its Philox words with its
+//                neighbour lane (one call per eight coordinates, every load contiguous over the wave)
 // The loads of the next tile are issued before the current tile is rounded.
 // ---------------------------------------------------------------------------------------------------------
 template <int SCHEME, bool UNIFORM_HI, bool HALF, bool WHOLE>
@@ -303,7 +304,12 @@ __device__ __forceinline__ void quantize_span(const float *__restrict__ x, int64
     const int t = (int)threadIdx.x;
     int li[kVecs];
 #pragma unroll
-    for (int i = 0; i < kVecs; i++) li[i] = HALF ? 2 * (t + kCompactBlock * (i >> 1)) + (i & 1) : i * kCompactBlock + t;
+    for (int i = 0; i < kVecs; i++) {
+        // short draws: a wave takes chunks of 128 consecutive vectors, lane l owns vectors l and 64 + l of a chunk
+        // (see share_short_draws); wave w takes chunks w and w + 4 of the tile's eight
+        const int chunk = (t >> 6) + (kCompactBlock / 64) * (i >> 1);
+        li[i] = HALF ? chunk * 128 + 64 * (i & 1) + (t & 63) : i * kCompactBlock + t;
+    }
     auto load_tile = [&](int j, f32x4 *g) {
 #pragma unroll
         for (int i = 0; i < kVecs; i++) {
@@ -345,11 +351,12 @@ __device__ __forceinline__ void quantize_span(const float *__restrict__ x, int64
 #pragma unroll
             for (int h = 0; h < kVecs / 2; h++) {
                 uint32_t c_lo, c_hi;
-                counter(t + kCompactBlock * h, c_lo, c_hi);
-                const Words4 r = philox4x32_10(c_lo, c_hi, worker, 0u, k0, k1);
+                const int chunk = (t >> 6) + (kCompactBlock / 64) * h, lane = t & 63;
+                counter(chunk * 64 + (lane >> 1) + (lane & 1) * 32, c_lo, c_hi);
+                const ShortDraws sd = share_short_draws(philox4x32_10(c_lo, c_hi, worker, 0u, k0, k1), (lane & 1) != 0);
                 uint32_t da[4], db[4];
 #pragma unroll
-                for (int i = 0; i < 4; i++) { da[i] = short_draw(&r.w[0], i); db[i] = short_draw(&r.w[2], i); }
+                for (int i = 0; i < 4; i++) { da[i] = short_draw(sd.a, i); db[i] = short_draw(sd.b, i); }
                 emit(2 * h, da);
                 emit(2 * h + 1, db);
             }
