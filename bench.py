@@ -57,6 +57,10 @@ def parse():
                     help="write windows of the fused call in the timed steps: the library's policy, forced on, or forced off "
                          "(gq_params.flags); for profiling one variant at a time")
     ap.add_argument("--ab-rounds", type=int, default=15, help="rounds of the write-window A/B (each times off, then on)")
+    ap.add_argument("--workers", type=int, default=None,
+                    help="override the workload's worker count K (1..64): the same value distribution at another shape, for sweeps")
+    ap.add_argument("--coords", type=int, default=None,
+                    help="override the workload's coordinates per worker d (not for the bucketed workload)")
     ap.add_argument("--graph", action="store_true",
                     help="also capture the step in a HIP graph and time its replays (reported as graph_replay_ms_per_step)")
     return ap.parse_args()
@@ -223,6 +227,16 @@ def main():
     dev = torch.device("cuda:0")
     cfg = SI.CONFIGS[args.workload]
     K, d, s = cfg["K"], cfg["d"], cfg["s"]
+    own_shape = args.workers is None and args.coords is None
+    if not own_shape:
+        if cfg.get("bucket") and args.coords is not None:
+            print("bench.py: --coords is not offered for the bucketed workload", file=sys.stderr)
+            sys.exit(2)
+        K = args.workers if args.workers is not None else K
+        d = args.coords if args.coords is not None else d
+        if not (1 <= K <= 64) or d < 1:
+            print("bench.py: --workers must lie in 1..64 and --coords be positive", file=sys.stderr)
+            sys.exit(2)
     scheme = gq.GQ_LINEAR if cfg["scheme"] == "linear" else gq.GQ_EXP
     if args.norm:
         cfg = dict(cfg, norm=args.norm)
@@ -230,7 +244,7 @@ def main():
     win_flags = {"default": 0, "on": gq.GQ_FLAG_WRITE_WINDOWS_ON, "off": gq.GQ_FLAG_WRITE_WINDOWS_OFF}[args.windows]
     params = gq.make_params(scheme, s, gq.GQ_PACK_I8, gq.GQ_AGG_I32, seed=SI.QUANT_SEED, flags=win_flags)
 
-    xs = SI.make_workers(args.workload, device=dev)
+    xs = SI.make_workers(args.workload, d=d, K=K, device=dev)
     norm = torch.zeros(1, device=dev)
     flags = torch.zeros(1, dtype=torch.int32, device=dev)
     ws = torch.empty(gq.norm_workspace_bytes(K, d), dtype=torch.uint8, device=dev)
@@ -338,7 +352,7 @@ def main():
                       "note": "interleaved off/on calls after the timed steps; the headline is the library's default policy"}
 
     traffic = valu_busy = traffic_note = None
-    if args.workload == "c3" and os.path.exists(TRAFFIC_FILE):
+    if args.workload == "c3" and own_shape and os.path.exists(TRAFFIC_FILE):
         # rocprofv3 cannot run inside this process: the HBM byte counts were profiled offline, and the file says on
         # which library version; figures of another version are not reported
         try:
@@ -355,7 +369,7 @@ def main():
             traffic_note = "traffic figures unreadable: %r" % (e,)
 
     line = {
-        "metric": ("fused quantize+aggregate GB/s and % of HBM peak, d=110M K=16 fp32" if args.workload == "c3" else
+        "metric": ("fused quantize+aggregate GB/s and % of HBM peak, d=110M K=16 fp32" if args.workload == "c3" and own_shape else
                    "fused quantize+aggregate GB/s and %% of HBM peak, workload %s (d=%d K=%d fp32)" % (args.workload, d, K)),
         "value": fused_gbps, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
