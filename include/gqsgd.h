@@ -44,8 +44,8 @@
  * (lo32(g/8), hi32(g/8), worker, 0); coordinate g takes the low (g even) or high (g odd) half of word
  * (g mod 8) / 2 as the TOP half of r, zeros below, and the two rules apply unchanged: the probability
  * of Eq. (2) is then met to 2^-16 and the generator costs half as much per coordinate.  index_base
- * must then be a multiple of 8.  Only gq_quantize and gq_fused_quantize_aggregate draw from this
- * stream; the other calls ignore rng_bits.
+ * must then be a multiple of 8.  Only gq_quantize, gq_quantize_compact and gq_fused_quantize_aggregate (and the
+ * per-bucket schedule built on it) draw from this stream; the other calls ignore rng_bits.
  * A norm that is zero, negative or not finite (or so small that the scale overflows) gives all-zero codes, also at
  * NaN or Inf coordinates.  Under a usable norm a NaN coordinate gives code 0 and |x| > norm the top level.
  */

@@ -202,3 +202,21 @@ def test_argument_checks_need_no_device(gq):
     assert sa(P(gq.GQ_LINEAR, 127, agg=gq.GQ_AGG_I16)) == gq.GQ_ERR_UNSUPPORTED
     assert sa(ok, K=0) == I and sa(ok, idx=None) == I and sa(ok, agg=odd) == I and sa(ok, d=1 << 33) == I
     assert sa(ok, idx=(C.c_void_p * 2)(0x1000, 0x2002)) == I
+
+
+def test_header_is_plain_c_and_cxx(tmp_path):
+    # the boundary is a C ABI: include/gqsgd.h compiles on its own as C99 and as C++17, with no torch or HIP types
+    import shutil
+    import subprocess
+    for compiler, std, ext in (("gcc", "-std=c99", "c"), ("g++", "-std=c++17", "cpp")):
+        exe = shutil.which(compiler)
+        if exe is None:
+            pytest.skip("no " + compiler)
+        src = tmp_path / ("use_header." + ext)
+        src.write_text('#include "gqsgd.h"\n'
+                       'int use(void) { gq_params p; p.flags = GQ_FLAG_WRITE_WINDOWS_OFF; return (int)sizeof(p) + (int)GQ_OK + GQ_MAX_WORKERS; }\n')
+        res = subprocess.run([exe, std, "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", "-I", os.path.join(ROOT, "include"), str(src)],
+                             stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        assert res.returncode == 0, res.stdout
+    text = open(HEADER).read()
+    assert "torch" not in text and "#include <hip" not in text and "#include \"hip" not in text
