@@ -20,6 +20,7 @@
  *   Implementation section  low-bit linear codes averaged inside every reduce step -> gqo_avg_pair, gqo_avg_tree_reduce,
  *                                                                                     gqo_avg_reduce_dequantize
  *   Algorithm 1, sparse branch: only the non-zero codes are exchanged              -> gqo_compact, gqo_sparse_aggregate
+ *   Theorem 1, sparsity statement (in the form Eq. (2) implies)                      -> gqo_sparse_nnz_bound
  *
  * Stored level integer ("code").  The paper numbers levels downwards, l_0 = 1 > ... > l_s = 0.
  * The integer that is stored and summed is k = s - u for level l_u, so k = 0 is the zero level:
@@ -548,6 +549,23 @@ void gqo_avg_reduce_dequantize(const int32_t *code, int64_t d, double norm, int 
  * codes with their coordinate indices, in increasing index order; what every receiver forms from
  * the K lists is the same integer sum as the dense aggregate.
  * ========================================================================================== */
+
+/* Theorem 1's sparsity statement under the (2,2) norm, in the form that follows from Eq. (2).  Let top = s (linear grid)
+ * or 2^(s-1) (exponential grid), so that 1/top is the smallest non-zero level.  Since the squares of all K d values of y sum
+ * to at most 1, at most top^2 coordinates have y >= 1/top; every other coordinate is non-zero with probability top * y; and
+ * the sum of all y is at most sqrt(K d).  Hence
+ *     E[number of non-zero codes over all K workers]  <=  top^2 + top * sqrt(K d),
+ * and never more than K d.  (The statement as printed has sqrt(nd) without the factor top.)  Returns -1 for arguments
+ * outside the grids' ranges. */
+double gqo_sparse_nnz_bound(int scheme, int s, int K, int64_t d)
+{
+    if ((scheme != 0 && scheme != 1) || s < 1 || K < 1 || d < 0) return -1.0;
+    if (scheme == 1 && s > 31) return -1.0;
+    double top = scheme == 0 ? (double)s : ldexp(1.0, s - 1);
+    double all = (double)K * (double)d;
+    double bound = top * top + top * sqrt(all);
+    return bound < all ? bound : all;
+}
 
 /* Returns the number of non-zero codes; writes at most `capacity` (index, code) pairs. */
 int64_t gqo_compact(const int32_t *q, int64_t d, int64_t capacity, uint32_t *index_out, int32_t *code_out)

@@ -71,6 +71,7 @@ _avg_reduce_dequantize = _sig("gqo_avg_reduce_dequantize", None, _i32p, C.c_int6
 
 
 _compact = _sig("gqo_compact", C.c_int64, _i32p, C.c_int64, C.c_int64, _u32p, _i32p)
+_sparse_nnz_bound = _sig("gqo_sparse_nnz_bound", C.c_double, C.c_int, C.c_int, C.c_int, C.c_int64)
 _sparse_aggregate = _sig("gqo_sparse_aggregate", None, C.POINTER(_u32p), C.POINTER(_i32p), _i64p, C.c_int, C.c_int64,
                          C.c_int, _i64p)
 
@@ -282,6 +283,12 @@ def compact(q, capacity=None):
     n = int(_compact(_ptr(q, C.c_int32), q.shape[0], cap, _ptr(idx, C.c_uint32), _ptr(val, C.c_int32)))
     m = min(n, cap)
     return n, idx[:m].copy(), val[:m].copy()
+
+
+def sparse_nnz_bound(scheme, s, K, d):
+    """Theorem 1's sparsity statement as Eq. (2) implies it: E[non-zero codes over all K workers] <= top^2 + top*sqrt(K d)
+    under the (2,2) norm, top = s or 2^(s-1); capped at K d; -1 for invalid arguments."""
+    return float(_sparse_nnz_bound(int(scheme), int(s), int(K), int(d)))
 
 
 def sparse_aggregate(indices, codes, d, scheme):

@@ -48,6 +48,7 @@ void gqo_avg_reduce_dequantize(const int32_t *code, int64_t d, double norm, int 
 int64_t gqo_compact(const int32_t *q, int64_t d, int64_t capacity, uint32_t *index_out, int32_t *code_out);
 void gqo_sparse_aggregate(const uint32_t *const *index, const int32_t *const *code, const int64_t *count, int K,
                           int64_t d, int scheme, int64_t *A);
+double gqo_sparse_nnz_bound(int scheme, int s, int K, int64_t d);
 
 static int failures = 0;
 #define CHECK(cond) do { if (!(cond)) { fprintf(stderr, "check failed line %d: %s\n", __LINE__, #cond); failures++; } } while (0)
@@ -193,6 +194,11 @@ int main(void)
             }
     CHECK(gqo_code_value(1, 31) == ((int64_t)1 << 30) && gqo_code_value(1, -31) == -((int64_t)1 << 30));
     CHECK(gqo_code_value(0, -32767) == -32767 && gqo_code_value(1, 0) == 0);
+
+    /* the sparsity bound at the ends of its ranges */
+    CHECK(gqo_sparse_nnz_bound(0, 32767, 64, ((int64_t)1 << 40)) > 0.0 && gqo_sparse_nnz_bound(1, 31, 64, ((int64_t)1 << 40)) > 0.0);
+    CHECK(gqo_sparse_nnz_bound(0, 1, 1, 0) == 0.0 && gqo_sparse_nnz_bound(1, 32, 1, 1) == -1.0 && gqo_sparse_nnz_bound(0, 0, 1, 1) == -1.0);
+    CHECK(gqo_sparse_nnz_bound(0, 4, 4, 1024) == 272.0 && gqo_sparse_nnz_bound(0, 1, 1, -1) == -1.0);
 
     /* headroom rule at the ends */
     CHECK(gqo_max_aggregate(0, 32767, 64) == 64 * 32767 && gqo_max_aggregate(1, 31, 64) == (int64_t)64 << 30);
