@@ -206,6 +206,9 @@ def time_rows(gq, torch, xs, norm, params, cfg, args):
             rows["sparse_aggregate"] = timed(lambda: gq.sparse_aggregate(idxs, vals, cnts, d, p, agg, tile_starts=tabs), 4.0 * d + 5.0 * tot)
             rows["sparse_aggregate_searching"] = timed(lambda: gq.sparse_aggregate(idxs, vals, cnts, d, p, agg), 4.0 * d + 5.0 * tot)
         rows["nonzero_fraction"] = tot / (float(K) * d)
+        if cfg["norm"] == "l2":
+            # Theorem 1's regime: the bound on the expected count that the lists can be sized by
+            rows["nonzero_fraction_bound"] = gq.sparse_nnz_bound(p, K, d) / (float(K) * d)
     rows["formats"] = {"pack": cfg["pack"], "agg": cfg["agg"]}
     return rows
 

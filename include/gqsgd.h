@@ -122,6 +122,15 @@ const char *gq_status_string(gq_status st);
  * GQ_ERR_INVALID_ARG for bad parameters.  Host only, touches no device. */
 gq_status gq_check_width(const gq_params *p /* host */, int K);
 
+/* Theorem 1's sparsity statement, in the form that follows from Eq. (2): an upper bound on the EXPECTED number of
+ * non-zero codes over all K workers of d coordinates when the norm is the (2,2) norm (GQ_NORM_L2),
+ *     unit^2 + unit * sqrt(K d),   unit = s (linear) or 2^(s-1) (exponential), never more than K d
+ * (at most unit^2 coordinates reach the smallest non-zero level 1/unit; every other one is non-zero with probability
+ * unit * y; the y of all coordinates sum to at most sqrt(K d)).  What a caller sizes the lists of the sparse branch by
+ * before the first call; the count returned by gq_compact / gq_quantize_compact says whether a list was large enough.
+ * Under the other norms no such bound holds.  Host only; -1 for bad parameters. */
+double gq_sparse_nnz_bound(const gq_params *p /* host */, int K, int64_t d);
+
 /* Bytes of device workspace gq_global_norm needs for (K, d); 0 if K or d is out of range. */
 size_t gq_norm_workspace_bytes(int K, int64_t d);
 

@@ -8,5 +8,5 @@ from .binding import (  # noqa: F401
     GQ_ERR_WORKSPACE, GQ_EXP, GQ_LINEAR, GQ_MAX_WORKERS, GQ_NORM_L2, GQ_NORM_L2_MAX, GQ_NORM_LINF, GQ_OK,
     GQ_PACK_I4, GQ_PACK_I8, GQ_PACK_U4_SIGNPLANE, GQ_PACK_U8_SIGNPLANE, GQError, avg_reduce, bucketed_quantize_aggregate, bucketed_workspace_bytes, check_width, compact, compact_workspace_bytes, dequantize, exp_reduce, sparse_aggregate,
     fused_quantize_aggregate, global_norm, global_norm_static, gq_params, int_aggregate, levels_nbytes, lib, make_params,
-    norm_workspace_bytes, quantize, quantize_compact, signplane_nwords, status_string, tile_starts_len, version,
+    norm_workspace_bytes, quantize, quantize_compact, signplane_nwords, sparse_nnz_bound, status_string, tile_starts_len, version,
 )

@@ -21,7 +21,7 @@ GQ_AGG_I32, GQ_AGG_I16 = 0, 1
 GQ_FLAG_WRITE_WINDOWS_OFF, GQ_FLAG_WRITE_WINDOWS_ON = 1, 2
 
 # every symbol include/gqsgd.h declares
-EXPORTS = ("gq_version", "gq_status_string", "gq_check_width", "gq_norm_workspace_bytes", "gq_global_norm",
+EXPORTS = ("gq_version", "gq_status_string", "gq_check_width", "gq_sparse_nnz_bound", "gq_norm_workspace_bytes", "gq_global_norm",
            "gq_global_norm_static", "gq_bucketed_workspace_bytes", "gq_bucketed_quantize_aggregate",
            "gq_quantize", "gq_int_aggregate", "gq_dequantize", "gq_fused_quantize_aggregate", "gq_exp_reduce", "gq_avg_reduce", "gq_compact_workspace_bytes", "gq_tile_starts_len", "gq_compact",
            "gq_quantize_compact",
@@ -51,6 +51,7 @@ def _load():
         "gq_version": (C.c_int, []),
         "gq_status_string": (C.c_char_p, [i32]),
         "gq_check_width": (i32, [pp, i32]),
+        "gq_sparse_nnz_bound": (C.c_double, [pp, i32, i64]),
         "gq_norm_workspace_bytes": (sz, [i32, i64]),
         "gq_global_norm": (i32, [C.POINTER(vp), i32, i64, i32, vp, vp, vp, sz, vp]),
         "gq_global_norm_static": (i32, [C.POINTER(vp), i32, i64, i32, vp, vp, vp]),
@@ -165,6 +166,11 @@ def version():
 def check_width(params, K):
     """gq_check_width: the status code (GQ_OK / GQ_ERR_OVERFLOW / ...), not an exception."""
     return int(_lib.gq_check_width(C.byref(params), int(K)))
+
+
+def sparse_nnz_bound(params, K, d):
+    """gq_sparse_nnz_bound: the bound on the expected number of non-zero codes under the (2,2) norm; -1 for bad parameters."""
+    return float(_lib.gq_sparse_nnz_bound(C.byref(params), int(K), int(d)))
 
 
 def norm_workspace_bytes(K, d):

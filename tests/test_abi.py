@@ -204,6 +204,21 @@ def test_argument_checks_need_no_device(gq):
     assert sa(ok, idx=(C.c_void_p * 2)(0x1000, 0x2002)) == I
 
 
+def test_sparsity_bound_matches_the_oracle(gq):
+    # host-only, like the headroom rule: the library's value against the oracle's over both grids and the ends of the ranges
+    from oracle import gq_oracle as O
+    for scheme, ss in ((gq.GQ_LINEAR, (1, 4, 15, 127, 255, 32767)), (gq.GQ_EXP, (1, 4, 7, 16, 31))):
+        for s in ss:
+            for K in (1, 3, 16, 64):
+                for d in (0, 1, 100, 1 << 20, 110_000_000, (1 << 34) - 1024):
+                    p = gq.make_params(scheme, s, gq.GQ_PACK_I8 if s <= 127 else gq.GQ_PACK_U8_SIGNPLANE)
+                    assert gq.sparse_nnz_bound(p, K, d) == O.sparse_nnz_bound(scheme, s, K, d), (scheme, s, K, d)
+    ok = gq.make_params(gq.GQ_LINEAR, 127)
+    assert gq.sparse_nnz_bound(ok, 0, 10) == -1.0 and gq.sparse_nnz_bound(ok, 65, 10) == -1.0 and gq.sparse_nnz_bound(ok, 1, -1) == -1.0
+    assert gq.sparse_nnz_bound(gq.make_params(gq.GQ_EXP, 32), 1, 10) == -1.0 and gq.sparse_nnz_bound(gq.make_params(2, 4), 1, 10) == -1.0
+    assert gq.sparse_nnz_bound(gq.make_params(gq.GQ_LINEAR, 4), 4, 1024) == 272.0
+
+
 def test_header_is_plain_c_and_cxx(tmp_path):
     # the boundary is a C ABI: include/gqsgd.h compiles on its own as C99 and as C++17, with no torch or HIP types
     import shutil

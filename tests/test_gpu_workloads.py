@@ -293,6 +293,7 @@ def test_workload_c3_sparse_branch_at_full_size(kind):
     assert (0.10 < frac < 0.25) if kind == "linf" else (0.0002 < frac < 0.002)      # about 16 % and 0.05 %
     if kind == "l2":
         assert total <= 1.2 * (s * s + s * np.sqrt(float(K) * d))               # the bound Eq. (2) implies
+        assert gq.sparse_nnz_bound(p, K, d) == s * s + s * np.sqrt(float(K) * d)  # and what the library sizes lists by
     # the receiver: the K lists add up to the dense integer sum over every coordinate, and to the oracle's on windows
     agg = torch.full((d + 8,), 0x5A5A, dtype=torch.int32, device=DEV)
     gq.sparse_aggregate(idxs, vals, cnts, d, p, agg)
