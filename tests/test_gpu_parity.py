@@ -863,6 +863,49 @@ def test_quantize_compact_bucket_offsets_unusable_norm_and_short_buffers():
     assert int(cnt4.item()) == 0
 
 
+def test_quantize_compact_equals_the_two_calls_on_random_shapes():
+    # 150 seeded cases over lengths (1 .. 3e6), both grids, every s, both draw widths, bucket offsets up to and across the
+    # points where the Philox call index passes 2^32, scaled and zero-riddled gradients, norms above and below the largest
+    # coordinate: list, count, table and guard entries are those of gq_quantize followed by gq_compact, bit for bit
+    # (which the tests above compare with the oracle)
+    rng = np.random.default_rng(7)
+    g = torch.Generator(device=DEV).manual_seed(5)
+    for it in range(150):
+        d = int(rng.choice([rng.integers(1, 70), rng.integers(1, 40_000), rng.integers(1, 3_000_000)]))
+        scheme = int(rng.integers(0, 2))
+        s = int(rng.integers(1, 128)) if scheme == 0 else int(rng.integers(1, 32))
+        bits = int(rng.choice([32, 16]))
+        base = int(rng.integers(0, 1 << 33)) * 8
+        if rng.random() < 0.2:
+            base = max((1 << (34 if bits == 32 else 35)) - 8 * int(rng.integers(0, d // 8 + 2)), 0)
+        worker = int(rng.integers(0, 64))
+        x = torch.randn(d, generator=g, device=DEV) * float(10 ** rng.uniform(-6, 0))
+        if rng.random() < 0.3:
+            x[torch.rand(d, generator=g, device=DEV) < 0.9] = 0.0
+        norm = torch.zeros(1, device=DEV)
+        gq.global_norm([x], int(rng.integers(0, 2)), norm, torch.zeros(1, dtype=torch.int32, device=DEV))
+        if rng.random() < 0.3:
+            norm *= float(rng.uniform(0.3, 30))
+        p = gq.make_params(scheme, s, 0, 0, seed=int(rng.integers(0, 1 << 62)), rng_bits=bits)
+        lv = torch.empty(d, dtype=torch.uint8, device=DEV)
+        gq.quantize(x, norm, p, worker, base, lv)
+        outs = []
+        for fused in (False, True):
+            idx = torch.full((d + 3,), -1, dtype=torch.int32, device=DEV)
+            val = torch.full((d + 3,), 0x5A, dtype=torch.int8, device=DEV)
+            cnt = torch.full((1,), -1, dtype=torch.int64, device=DEV)
+            tab = torch.full((gq.tile_starts_len(d) + 2,), -1, dtype=torch.int32, device=DEV)
+            if fused:
+                gq.quantize_compact(x, norm, p, worker, base, idx, val, cnt, tile_starts_out=tab)
+            else:
+                gq.compact(lv, d, p, idx, val, cnt, tile_starts_out=tab)
+            outs.append((idx, val, cnt, tab))
+        torch.cuda.synchronize()
+        case = (it, d, scheme, s, bits, base, worker)
+        assert all(torch.equal(a, b) for a, b in zip(outs[0], outs[1])), case
+        assert int(outs[0][2].item()) == int(torch.count_nonzero(lv)), case
+
+
 @pytest.mark.parametrize("scheme,s,kind", [("linear", 15, "l2"), ("linear", 127, "linf"), ("exp", 7, "l2")])
 @pytest.mark.parametrize("K,d", [(1, 1000), (4, 70_001), (16, 300_000)])
 def test_sparse_path_equals_dense_aggregate(scheme, s, kind, K, d):
