@@ -483,6 +483,52 @@ def test_fused_equals_separate_calls_and_buckets_equal_whole():
         assert torch.equal(agg2, agg)
 
 
+def test_fused_equals_separate_calls_on_random_shapes():
+    # 120 seeded cases over worker counts 1..64 (the specialised 4, 8, 16, 32 and the run-time path), ragged lengths,
+    # both grids, all four storage formats, both sum widths, both draw widths, bucket offsets, with and without stored
+    # codes: the fused call writes the codes of gq_quantize, the sum of gq_int_aggregate and the mean of gq_dequantize,
+    # bit for bit (each of which the tests above compare with the oracle at fixed shapes)
+    rng = np.random.default_rng(11)
+    g = torch.Generator(device=DEV).manual_seed(13)
+    done = 0
+    while done < 120:
+        K = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 12, 16, 17, 24, 32, 33, 48, 64]))
+        d = int(rng.choice([rng.integers(1, 40), rng.integers(1, 5000), rng.integers(1, 200_000)]))
+        scheme = int(rng.integers(0, 2))
+        pack = int(rng.integers(0, 4))
+        smax = (127, 7, 255, 15)[pack] if scheme == 0 else min((127, 7, 255, 15)[pack], 31)
+        s = int(rng.integers(1, smax + 1))
+        aggf = int(rng.integers(0, 2))
+        bits = int(rng.choice([32, 16]))
+        p = gq.make_params(scheme, s, pack, aggf, seed=int(rng.integers(0, 1 << 62)), rng_bits=bits)
+        if gq.check_width(p, K) != gq.GQ_OK:
+            continue                                                  # this sum does not fit this width: another draw
+        done += 1
+        base = int(rng.integers(0, 1 << 30)) * 8
+        xs = [torch.randn(d, generator=g, device=DEV) * float(10 ** rng.uniform(-5, 0)) for _ in range(K)]
+        norm_t = dev_scalar(0.0)
+        gq.global_norm(xs, int(rng.integers(0, 3)), norm_t)
+        case = (done, K, d, scheme, s, pack, aggf, bits, base)
+        with_codes = bool(rng.integers(0, 2))
+        agg_out, deq_out, lvs, sps = run_fused(xs, norm_t, p, base, with_codes)
+        # separate calls
+        qlv, qsp = [], []
+        for i in range(K):
+            lv, sp = gpu_quantize(xs[i], norm_t, p, i, base)
+            qlv.append(lv); qsp.append(sp)
+        agg = torch.full((d + 8,), 0x5A5A, dtype=torch.int16 if aggf else torch.int32, device=DEV)
+        gq.int_aggregate(qlv, qsp if qsp[0] is not None else None, d, p, agg)          # the guard entries behind d must survive
+        deq = torch.full((d + 8,), 7.0, device=DEV)
+        gq.dequantize(agg, d, norm_t, p, K, deq)
+        torch.cuda.synchronize()
+        assert torch.equal(agg, agg_out) and torch.equal(deq, deq_out), case
+        if with_codes:
+            for i in range(K):
+                assert torch.equal(lvs[i], qlv[i]), case
+                if qsp[i] is not None:
+                    assert torch.equal(sps[i], qsp[i]), case
+
+
 def test_fused_across_the_2_to_34_index_boundary():
     # the Philox call index g/4 crosses a multiple of 2^32 inside the bucket: the high counter word changes
     K, d = 16, 70_001
