@@ -529,6 +529,66 @@ def test_fused_equals_separate_calls_on_random_shapes():
                     assert torch.equal(sps[i], qsp[i]), case
 
 
+@pytest.mark.parametrize("scheme,s,pack", [("linear", 127, "i8"), ("linear", 15, "u4s"), ("exp", 7, "i4"), ("exp", 16, "i8")])
+@pytest.mark.parametrize("K,d,bucket", [(1, 8, 8), (3, 1000, 4096), (4, 4096, 1024), (5, 70_001, 8192), (8, 20_003, 20_000), (16, 33_000, 32_768)])
+def test_per_bucket_schedule_matches_the_oracle_bucket_by_bucket(scheme, s, pack, K, d, bucket):
+    # gq_bucketed_quantize_aggregate at small sizes: one bucket, whole buckets only, a last bucket of a few coordinates.
+    # Every bucket's norm against the oracle's norm of the K slices; the sums against the oracle's quantisation under
+    # that norm and the bucket's offset; the means to 1e-5; both schedules identical; guard entries untouched
+    xs = gaussians(K, d, seed=K + d + s)
+    xh = [host(x) for x in xs]
+    nb = (d + bucket - 1) // bucket
+    p = gq.make_params(SCHEMES[scheme], s, PACKS[pack], 0, seed=2025)
+    side = torch.cuda.Stream()
+    means = {}
+    for kind in ("linf", "l2", "l2max"):
+        got = []
+        for two in (False, True):
+            norms = torch.full((nb + 2,), -1.0, device=DEV)
+            flags = torch.full((nb + 2,), 77, dtype=torch.int32, device=DEV)
+            agg = torch.full((d + 8,), 0x5A5A, dtype=torch.int32, device=DEV)
+            out = torch.full((d + 8,), 7.0, device=DEV)
+            gq.bucketed_quantize_aggregate(xs, bucket, NORMS[kind], p, norms, flags, agg, out, side_stream=side if two else None)
+            torch.cuda.synchronize()
+            got.append((norms, flags, agg, out))
+        for a, b in zip(got[0], got[1]):
+            assert torch.equal(a, b)
+        norms, flags, agg, out = got[0]
+        means[kind] = out
+        assert bool((norms[nb:] == -1.0).all()) and bool((flags[nb:] == 77).all()) and bool((flags[:nb] == 0).all())
+        assert bool((agg[d:] == 0x5A5A).all()) and bool((out[d:] == 7.0).all())
+        for b in range(nb):
+            lo, hi = b * bucket, min(d, (b + 1) * bucket)
+            _, nf, _ = O.global_norm([x[lo:hi] for x in xh], NORMS[kind])
+            gn = np.float32(norms[b].item())
+            if kind == "linf":
+                assert gn == nf
+            else:
+                assert abs(float(gn) - float(nf)) <= RTOL * float(nf)
+            # the codes are decided under the library's own norm of the bucket (one ulp of norm can move a code)
+            A = O.quantize_aggregate([x[lo:hi] for x in xh], gn, SCHEMES[scheme], s, 2025, lo)
+            assert np.array_equal(host(agg[lo:hi]).astype(np.int64), A), (kind, b)
+            wd = O.dequantize(A, float(gn), SCHEMES[scheme], s, K)
+            gd = host(out[lo:hi]).astype(np.float64)
+            assert np.all(np.abs(gd - wd) <= RTOL * np.abs(wd)) and np.all(gd[A == 0] == 0.0)
+    # one output may be left out; neither is an error, and so are a bucket that is no multiple of 8 and a short workspace
+    norms = torch.zeros(nb, device=DEV)
+    only = torch.zeros(d, device=DEV)
+    gq.bucketed_quantize_aggregate(xs, bucket, NORMS["linf"], p, norms, None, None, only)
+    torch.cuda.synchronize()
+    assert torch.equal(only, means["linf"][:d])
+    for bad_call in (lambda: gq.bucketed_quantize_aggregate(xs, bucket, NORMS["linf"], p, norms, None, None, None),
+                     lambda: gq.bucketed_quantize_aggregate(xs, bucket + 4, NORMS["linf"], p, norms, None, None, only),
+                     lambda: gq.bucketed_quantize_aggregate(xs, 0, NORMS["linf"], p, norms, None, None, only)):
+        with pytest.raises((gq.GQError, ValueError, ZeroDivisionError)):
+            bad_call()
+    if gq.bucketed_workspace_bytes(K, d, bucket) > 8:
+        with pytest.raises(gq.GQError) as e:
+            gq.bucketed_quantize_aggregate(xs, bucket, NORMS["linf"], p, norms, None, None, only,
+                                           workspace=torch.zeros(8, dtype=torch.uint8, device=DEV))
+        assert e.value.status == gq.GQ_ERR_WORKSPACE
+
+
 def test_fused_across_the_2_to_34_index_boundary():
     # the Philox call index g/4 crosses a multiple of 2^32 inside the bucket: the high counter word changes
     K, d = 16, 70_001
